@@ -1,0 +1,198 @@
+"""SharpV two-stage pruning, written out from the paper's definitions in float64 (NumPy).
+
+TEST INFRASTRUCTURE ONLY.  This is the slow, plain checker that the GPU library is compared
+against; nothing in the product path may import it.  It shares no code with the HIP
+kernels and takes its inputs as plain NumPy arrays.
+
+Every function follows one passage of the paper (Sec. 3.1 "Information-Aware Visual Space
+Pruning", Sec. 3.2 "Information-Aware Memory Space Pruning"); equation numbers count the
+displayed equations in order of appearance: Eq.1 Dissim, Eq.2 spatial importance S, Eq.3
+temporal importance T, Eq.4 score I, Eq.5 threshold_t, Eq.6 threshold_1, Eq.7 Discard(l).
+
+Readings taken where the paper is silent (each is listed with its reason in the design notes):
+  * thresholds of Eq.5/6 are *retention* ratios; kept count k_t = floor(r_t*f + 1/2),
+    clamped to [min_keep, f];
+  * the first frame of a video uses T := S (the virtual preceding frame of Sec. 3.1 whose
+    every token is the frame mean), so Eq.6 is Eq.5 applied to that T;
+  * a zero-norm vector has cosine 0 to everything;
+  * top-k ties go to the lowest token index, kept tokens stay in stream order;
+  * Eq.7 is applied per visual token (kv_mode 0) or to the mean over a sequence's visual
+    tokens (kv_mode 1); non-visual positions are always kept; "< M" is strict.
+
+Pins: tests/test_oracle_pins.py (closed forms, invariants, brute force, library routines).
+No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, Optional
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------- widening
+def widen(a: np.ndarray, dtype: int) -> np.ndarray:
+    """Storage array -> float64, exactly.  dtype 0: float32; dtype 1: bfloat16 bit patterns (uint16)."""
+    if dtype == 0:
+        return np.asarray(a, dtype=np.float32).astype(np.float64)
+    bits = np.asarray(a, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return bits.view(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------- Eq.1
+def cosine(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """cos(theta) between corresponding rows of a and b (b may be a single broadcast row).
+    A zero-norm row has cosine 0."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.broadcast_to(np.asarray(b, dtype=np.float64), a.shape)
+    na = np.sqrt(np.sum(a * a, axis=-1))
+    nb = np.sqrt(np.sum(b * b, axis=-1))
+    dot = np.sum(a * b, axis=-1)
+    den = na * nb
+    out = np.zeros_like(den)
+    np.divide(dot, den, out=out, where=den > 0)
+    return np.clip(out, -1.0, 1.0)
+
+
+def dissim(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Eq.1, first form: Euclidean distance between the L2-normalised rows.
+    (A zero-norm row is treated as having cosine 0, i.e. distance sqrt(2).)"""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.broadcast_to(np.asarray(b, dtype=np.float64), a.shape)
+    na = np.sqrt(np.sum(a * a, axis=-1, keepdims=True))
+    nb = np.sqrt(np.sum(b * b, axis=-1, keepdims=True))
+    ok = (na[..., 0] > 0) & (nb[..., 0] > 0)
+    ua = np.divide(a, na, out=np.zeros_like(a), where=na > 0)
+    ub = np.divide(b, nb, out=np.zeros_like(a), where=nb > 0)
+    dist = np.sqrt(np.sum((ua - ub) ** 2, axis=-1))
+    return np.where(ok, dist, math.sqrt(2.0))
+
+
+def dissim_from_cos(c: np.ndarray) -> np.ndarray:
+    """Eq.1, second form: sqrt(2 - 2 cos(theta))."""
+    return np.sqrt(np.maximum(0.0, 2.0 - 2.0 * np.asarray(c, dtype=np.float64)))
+
+
+# ----------------------------------------------------------------------------- Eq.2 - Eq.6
+def spatial_importance(frame: np.ndarray) -> np.ndarray:
+    """Eq.2: S_i = Dissim(F_t[i], mean_j F_t[j]); the mean row is broadcast over tokens."""
+    mean = np.mean(np.asarray(frame, dtype=np.float64), axis=0, keepdims=True)
+    return dissim(frame, mean)
+
+
+def temporal_importance(frame: np.ndarray, prev: np.ndarray) -> np.ndarray:
+    """Eq.3: T_i = Dissim(F_t[i], F_{t-1}[i]) -- the same token slot in adjacent frames."""
+    return dissim(frame, prev)
+
+
+def importance(T: np.ndarray, S: np.ndarray, w: float) -> np.ndarray:
+    """Eq.4: I = T + w*S."""
+    return T + w * S
+
+
+def keep_ratio(T_frame: np.ndarray) -> float:
+    """Eq.5 (and Eq.6 with T := S): ||T_t||_2 / (2 sqrt(f)), in [0, 1]."""
+    f = T_frame.shape[0]
+    r = math.sqrt(float(np.sum(T_frame * T_frame))) / (2.0 * math.sqrt(f))
+    return min(1.0, max(0.0, r))
+
+
+def kept_count(r: float, f: int, min_keep: int = 0) -> int:
+    """k_t = round-half-up(r_t * f), clamped to [min_keep, f]."""
+    return int(min(f, max(min_keep, math.floor(r * f + 0.5))))
+
+
+def select_topk(I: np.ndarray, k: int) -> np.ndarray:
+    """Top-k of one frame by score (Sec. 3.1, last paragraph).  Token i is kept iff fewer
+    than k tokens precede it in the order (score descending, index ascending).  Returns
+    the kept token indices in ascending order."""
+    I = np.asarray(I)
+    idx = np.arange(I.shape[0])
+    greater = (I[None, :] > I[:, None]).sum(axis=1)
+    tie_before = ((I[None, :] == I[:, None]) & (idx[None, :] < idx[:, None])).sum(axis=1)
+    return np.nonzero(greater + tie_before < k)[0]
+
+
+def prune_tokens(feats: np.ndarray, dtype: int, frame_offsets: np.ndarray, w: float = 1.0,
+                 mode: int = 0, K: float = 1.6, min_keep: int = 0) -> Dict[str, np.ndarray]:
+    """Pre-LLM stage over a packed batch of videos.
+
+    feats [n_total, f, d] storage array; frame_offsets [B+1] cumulative frames per video.
+    mode 0: adaptive ratio (Eq.5/6) + per-frame top-k; mode 1: keep token iff I >= K.
+    Returns S, T, I [n_total, f]; ratio [n_total]; counts [n_total]; offsets [n_total+1];
+    idx [sum k] global row indices t*f+i ascending; out_feats = the kept rows, bit-copied."""
+    n_total, f, d = feats.shape
+    x = widen(feats, dtype)
+    S = np.zeros((n_total, f))
+    T = np.zeros((n_total, f))
+    ratio = np.zeros(n_total)
+    counts = np.zeros(n_total, dtype=np.int32)
+    kept = []
+    for b in range(len(frame_offsets) - 1):
+        for t in range(int(frame_offsets[b]), int(frame_offsets[b + 1])):
+            S[t] = spatial_importance(x[t])
+            T[t] = S[t] if t == int(frame_offsets[b]) else temporal_importance(x[t], x[t - 1])
+    I = importance(T, S, w)
+    for t in range(n_total):
+        ratio[t] = keep_ratio(T[t])
+        if mode == 0:
+            sel = select_topk(I[t], kept_count(ratio[t], f, min_keep))
+        else:
+            sel = np.nonzero(I[t] >= K)[0]
+        counts[t] = len(sel)
+        kept.append(t * f + sel)
+    offsets = np.zeros(n_total + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    idx = np.concatenate(kept).astype(np.int32) if kept else np.zeros(0, np.int32)
+    out_feats = np.asarray(feats).reshape(n_total * f, d)[idx]
+    return {"S": S, "T": T, "I": I, "ratio": ratio, "counts": counts, "offsets": offsets,
+            "idx": idx, "out_feats": out_feats}
+
+
+# ----------------------------------------------------------------------------- Eq.7
+def prune_kv(hidden: np.ndarray, orig: np.ndarray, Kc: np.ndarray, Vc: np.ndarray, dtype: int,
+             seq_offsets: np.ndarray, vis_start: np.ndarray, vis_offsets: np.ndarray,
+             M: float = 0.2, kv_mode: int = 0) -> Dict[str, np.ndarray]:
+    """Intra-LLM stage for one layer over a packed batch of sequences (Sec. 3.2, Eq.7).
+
+    hidden [S, d] layer-l hidden states; orig [n_vis, d] original visual embeddings; Kc, Vc
+    [H, S, D].  Visual token p of sequence b sits at packed position
+    seq_offsets[b] + vis_start[b] + (p - vis_offsets[b]).
+    kv_mode 0: visual token discarded iff cos(hidden, orig) < M.
+    kv_mode 1: all visual tokens of a sequence discarded iff their mean cosine < M.
+    Returns cos [n_vis], mean_cos [B], idx (kept packed positions ascending), counts [B],
+    K_out, V_out [H, S_kept, D] bit-copied."""
+    S_total = hidden.shape[0]
+    B = len(vis_start)
+    h = widen(hidden, dtype)
+    o = widen(orig, dtype)
+    keep = np.ones(S_total, dtype=bool)
+    cos = np.zeros(o.shape[0])
+    mean_cos = np.zeros(B)
+    counts = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        lo, hi = int(vis_offsets[b]), int(vis_offsets[b + 1])
+        p0 = int(seq_offsets[b]) + int(vis_start[b])
+        c = cosine(h[p0:p0 + (hi - lo)], o[lo:hi])
+        cos[lo:hi] = c
+        mean_cos[b] = float(np.mean(c)) if hi > lo else 0.0
+        if kv_mode == 0:
+            keep[p0:p0 + (hi - lo)] = ~(c < M)
+        elif hi > lo and mean_cos[b] < M:
+            keep[p0:p0 + (hi - lo)] = False
+        counts[b] = int(keep[int(seq_offsets[b]):int(seq_offsets[b + 1])].sum())
+    idx = np.nonzero(keep)[0].astype(np.int32)
+    return {"cos": cos, "mean_cos": mean_cos, "idx": idx, "counts": counts,
+            "K_out": np.asarray(Kc)[:, idx, :], "V_out": np.asarray(Vc)[:, idx, :]}
+
+
+# ----------------------------------------------------------------------------- retention figures
+def retention(counts_tokens: np.ndarray, f: int, kept_kv: Optional[int] = None, S: Optional[int] = None) -> Dict[str, float]:
+    """VR = kept visual tokens / all visual tokens; MR = kept KV positions / all positions;
+    token budget = VR * MR (Sec. 4.1, Metrics)."""
+    vr = float(np.sum(counts_tokens)) / float(len(counts_tokens) * f)
+    out = {"VR": vr}
+    if kept_kv is not None and S:
+        out["MR"] = kept_kv / float(S)
+        out["budget"] = vr * out["MR"]
+    return out

@@ -1,0 +1,156 @@
+/*
+ * sharpv.h -- C ABI of the SharpV pruning library for AMD MI355X (gfx950).
+ *
+ * SharpV (Sec. 3 of the paper) prunes a VideoLLM's visual tokens in two places:
+ *
+ *   sharpv_prune_tokens   pre-LLM stage, Sec. 3.1 "Information-Aware Visual Space Pruning":
+ *                         spatial importance S (Eq.2) and temporal importance T (Eq.3) of every
+ *                         token through the dissimilarity of Eq.1, score I = T + w S (Eq.4), a
+ *                         per-frame retention ratio ||T_t||_2 / (2 sqrt f) (Eq.5; first frame of a
+ *                         video from S, Eq.6), per-frame top-k by I, and the compacted token stream.
+ *
+ *   sharpv_prune_kv       intra-LLM stage, Sec. 3.2 "Information-Aware Memory Space Pruning":
+ *                         cosine between each visual token's layer-l hidden state and its original
+ *                         embedding, discard when it is below M (Eq.7), and the layer's K/V cache
+ *                         gathered into a compacted cache.  Attention scores are never needed.
+ *
+ * Conventions (all entry points)
+ *   - Every tensor pointer is CALLER-OWNED DEVICE MEMORY on the current HIP device unless it is
+ *     marked "host".  The library never allocates, frees or keeps device memory; scratch space
+ *     comes from the caller's workspace (query the size first).  Base pointers of feats / hidden /
+ *     orig / K / V / their outputs must be 16-byte aligned, the workspace 256-byte aligned.
+ *   - Calls only ENQUEUE work on `stream` (a hipStream_t passed as void*; NULL = the null stream)
+ *     and return without synchronising.  Counts stay on the device, so output buffers are sized
+ *     for the worst case (everything kept).
+ *   - The return value is a sharpv_status.  Argument errors are found on the host before any
+ *     launch and leave every output untouched; nothing throws or aborts across this boundary.
+ *   - Inputs must be finite.  Scores are accumulated in float32 in a fixed order, so results do
+ *     not depend on launch geometry and repeat bit for bit.
+ *   - Overlapping calls that share a workspace race; calls on one stream are ordered.
+ */
+#ifndef SHARPV_H
+#define SHARPV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SHARPV_OK = 0,
+    SHARPV_ERR_NULL = 1,        /* a required pointer is NULL */
+    SHARPV_ERR_SHAPE = 2,       /* a size is out of range or violates an alignment rule */
+    SHARPV_ERR_DTYPE = 3,       /* params->dtype is not a sharpv_dtype */
+    SHARPV_ERR_PARAM = 4,       /* params->struct_size / mode / kv_mode / min_keep invalid */
+    SHARPV_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small */
+    SHARPV_ERR_DEVICE = 6       /* a HIP call or kernel launch failed */
+} sharpv_status;
+
+typedef enum { SHARPV_F32 = 0, SHARPV_BF16 = 1 } sharpv_dtype;
+
+/* Hyper-parameters (Sec. 4.1, Implementation Details: adaptive setting M = 0.2, w = 1; the
+ * semi-adaptive setting adds a fixed threshold K = 1.6). */
+typedef struct sharpv_params {
+    uint32_t struct_size;   /* = sizeof(sharpv_params); checked */
+    int32_t  dtype;         /* sharpv_dtype of feats / hidden / orig / K / V */
+    float    w;             /* Eq.4 weight of the spatial importance */
+    float    M;             /* Eq.7 degradation threshold */
+    int32_t  mode;          /* 0: adaptive retention ratio + per-frame top-k (Eq.5/6);
+                               1: keep token iff I >= K (manual threshold) */
+    float    K;             /* manual threshold, used when mode == 1 */
+    int32_t  min_keep;      /* lower clamp of the per-frame kept count (mode 0), 0 <= min_keep <= f */
+    int32_t  kv_mode;       /* 0: Eq.7 per visual token;
+                               1: Eq.7 on the mean cosine of a sequence's visual tokens (all or none) */
+} sharpv_params;
+
+/* Fills *p with the paper's defaults (bf16, w=1, M=0.2, mode 0, K=1.6, min_keep 0, kv_mode 0). */
+int sharpv_params_default(sharpv_params* p /* host */);
+
+/* Static, NUL-terminated description of a status code. */
+const char* sharpv_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int sharpv_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Pre-LLM stage (Sec. 3.1, Eq.1-6).
+ *
+ * feats is a packed batch of B videos: [n_frames, f, d] row-major, one token per row, where n_frames
+ * is the total over the batch and video b owns frames [frame_offsets[b], frame_offsets[b+1]).  The
+ * first frame of every video takes T := S (Eq.6); frames never look across a video boundary.
+ *
+ * Limits: 1 <= f <= 1024, d a positive multiple of 8, n_frames*f < 2^31, 1 <= B <= n_frames.
+ */
+size_t sharpv_prune_tokens_workspace(int n_frames, int f, int d, const sharpv_params* params /* host */);
+
+int sharpv_prune_tokens(
+    const void*    feats,          /* device [n_frames, f, d], params->dtype */
+    const int32_t* frame_offsets,  /* device [B+1] ascending, [0]=0, [B]=n_frames; NULL => one video (B must be 1) */
+    int B, int n_frames, int f, int d,
+    const sharpv_params* params,   /* host */
+    int32_t* out_idx,              /* device, capacity n_frames*f: kept global row indices t*f+i, ascending */
+    int32_t* out_counts,           /* device [n_frames]: kept tokens per frame */
+    int32_t* out_offsets,          /* device [n_frames+1]: exclusive scan of out_counts; last = total kept */
+    void*    out_feats,            /* device, capacity n_frames*f*d: rows [0, total kept) = feats[out_idx[j]] */
+    float*   out_scores,           /* device [n_frames*f] I (Eq.4), or NULL */
+    float*   out_ratio,            /* device [n_frames] retention ratio (Eq.5/6), or NULL */
+    void* workspace, size_t workspace_bytes,
+    void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Intra-LLM stage for one decoder layer (Sec. 3.2, Eq.7).
+ *
+ * hidden is the layer's hidden-state matrix of a packed batch of B sequences, [S, d]; sequence b owns
+ * packed positions [seq_offsets[b], seq_offsets[b+1]), its visual block starts vis_start[b] positions
+ * into the sequence and its original embeddings are rows [vis_offsets[b], vis_offsets[b+1]) of orig.
+ * With B == 1 the three arrays may be NULL and the scalars vis_start0 / n_vis describe the only
+ * sequence.  Positions outside the visual blocks (system and instruction tokens) are always kept.
+ *
+ * K and V are [H, S, D] with element strides kv_stride_h (between heads) and kv_stride_s (between
+ * positions), D contiguous.  K_out / V_out receive [H, S_kept, D] with head stride out_stride_h
+ * (>= S*D is always enough) and position stride D; they must not overlap K / V.
+ *
+ * Limits: d a positive multiple of 8; D*sizeof(element) and all strides*sizeof(element) multiples
+ * of 16; S < 2^31.
+ */
+size_t sharpv_prune_kv_workspace(int B, int S, int n_vis, const sharpv_params* params /* host */);
+
+int sharpv_prune_kv(
+    const void* hidden,            /* device [S, d] */
+    const void* orig,              /* device [n_vis, d] */
+    const void* K, const void* V,  /* device [H, S, D] (strided) */
+    int64_t kv_stride_h, int64_t kv_stride_s,
+    const int32_t* seq_offsets,    /* device [B+1] or NULL (B == 1) */
+    const int32_t* vis_start,      /* device [B]   or NULL (B == 1) */
+    const int32_t* vis_offsets,    /* device [B+1] or NULL (B == 1) */
+    int B, int S, int vis_start0, int n_vis, int d, int H, int D,
+    int layer,                     /* carried for the caller's bookkeeping; does not change the result */
+    const sharpv_params* params,   /* host */
+    int32_t* out_idx,              /* device, capacity S: kept packed positions, ascending */
+    int32_t* out_count,            /* device [B]: kept positions per sequence */
+    void* K_out, void* V_out,      /* device [H, <=S, D], head stride out_stride_h */
+    int64_t out_stride_h,
+    float* out_cos,                /* device [n_vis] cosine per visual token, or NULL */
+    float* out_mean_cos,           /* device [B] mean cosine per sequence, or NULL */
+    void* workspace, size_t workspace_bytes,
+    void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Per-kernel timing with HIP events on the launch stream (for benchmarks; off by default).
+ * While enabled, every kernel launch of the two entry points is bracketed by a pair of events
+ * taken from a pool of `max_launches` pairs (launches beyond the pool go untimed).
+ * sharpv_timing_read synchronises on the recorded events and returns, for the kernel with the
+ * given name, the number of timed launches and their summed duration in milliseconds.
+ * Kernel names: "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
+ * "kv_cosine", "kv_mean", "kv_gather".  Not thread-safe; one device.
+ */
+int sharpv_timing_enable(int max_launches);     /* creates the pool; resets earlier records */
+int sharpv_timing_disable(void);                /* destroys the pool */
+int sharpv_timing_read(const char* kernel_name, int* n_launches /* host */, double* total_ms /* host */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHARPV_H */

@@ -1,0 +1,247 @@
+// C ABI of libsharpv (declared in include/sharpv.h): argument validation on the host, then the
+// launch sequences of sharpv_tokens.hip / sharpv_kv.hip.  Also the optional event timing.
+#include <string.h>
+
+#include <vector>
+
+#include "sharpv_kernels.hpp"
+
+namespace sharpv {
+
+// ---------------------------------------------------------------------------- event timing
+namespace {
+struct TimingPool {
+    bool enabled = false;
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int> kernel;        // kernel id of each used pair
+    size_t used = 0;
+    bool open = false;              // a begin without its end yet
+} g_timing;
+
+const char* const kKernelNames[kNumKernels] = {"frame_mean", "token_dots", "frame_select", "count_scan",
+                                               "token_gather", "kv_cosine", "kv_mean", "kv_gather"};
+}  // namespace
+
+void timing_begin(int kernel, hipStream_t st) {
+    TimingPool& t = g_timing;
+    if (!t.enabled || t.used >= t.start.size()) { t.open = false; return; }
+    t.kernel[t.used] = kernel;
+    (void)hipEventRecord(t.start[t.used], st);
+    t.open = true;
+}
+
+void timing_end(int, hipStream_t st) {
+    TimingPool& t = g_timing;
+    if (!t.enabled || !t.open) return;
+    (void)hipEventRecord(t.stop[t.used], st);
+    ++t.used;
+    t.open = false;
+}
+
+static void timing_destroy() {
+    TimingPool& t = g_timing;
+    for (hipEvent_t e : t.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : t.stop) (void)hipEventDestroy(e);
+    t.start.clear();
+    t.stop.clear();
+    t.kernel.clear();
+    t.used = 0;
+    t.open = false;
+    t.enabled = false;
+}
+
+static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+static int check_params(const sharpv_params* p) {
+    if (p == nullptr) return SHARPV_ERR_NULL;
+    if (p->struct_size != sizeof(sharpv_params)) return SHARPV_ERR_PARAM;
+    if (p->dtype != SHARPV_F32 && p->dtype != SHARPV_BF16) return SHARPV_ERR_DTYPE;
+    if (p->mode != 0 && p->mode != 1) return SHARPV_ERR_PARAM;
+    if (p->kv_mode != 0 && p->kv_mode != 1) return SHARPV_ERR_PARAM;
+    if (p->min_keep < 0) return SHARPV_ERR_PARAM;
+    if (!(p->w == p->w) || !(p->M == p->M) || !(p->K == p->K)) return SHARPV_ERR_PARAM;   // NaN
+    return SHARPV_OK;
+}
+
+static int check_token_shape(int B, int n, int f, int d) {
+    if (n < 1 || f < 1 || f > 1024 || d < 8 || d % 8 != 0 || d > 65536) return SHARPV_ERR_SHAPE;
+    if (B < 1 || B > n) return SHARPV_ERR_SHAPE;
+    if ((long long)n * f >= (1ll << 31)) return SHARPV_ERR_SHAPE;
+    return SHARPV_OK;
+}
+
+static int check_kv_shape(int B, int S, int n_vis, int d) {
+    if (S < 1 || n_vis < 0 || n_vis > S || d < 8 || d % 8 != 0 || d > 65536) return SHARPV_ERR_SHAPE;
+    if (B < 1 || B > S) return SHARPV_ERR_SHAPE;
+    return SHARPV_OK;
+}
+
+}  // namespace sharpv
+
+using namespace sharpv;
+
+extern "C" {
+
+int sharpv_params_default(sharpv_params* p) {
+    if (p == nullptr) return SHARPV_ERR_NULL;
+    memset(p, 0, sizeof(*p));
+    p->struct_size = (uint32_t)sizeof(sharpv_params);
+    p->dtype = SHARPV_BF16;
+    p->w = 1.0f;
+    p->M = 0.2f;
+    p->mode = 0;
+    p->K = 1.6f;
+    p->min_keep = 0;
+    p->kv_mode = 0;
+    return SHARPV_OK;
+}
+
+const char* sharpv_status_string(int status) {
+    switch (status) {
+        case SHARPV_OK: return "ok";
+        case SHARPV_ERR_NULL: return "a required pointer is NULL";
+        case SHARPV_ERR_SHAPE: return "a size is out of range or breaks an alignment rule";
+        case SHARPV_ERR_DTYPE: return "unknown element type";
+        case SHARPV_ERR_PARAM: return "invalid parameter block";
+        case SHARPV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SHARPV_ERR_DEVICE: return "HIP call or kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int sharpv_version(void) { return 100; }
+
+size_t sharpv_prune_tokens_workspace(int n_frames, int f, int d, const sharpv_params* params) {
+    if (check_params(params) != SHARPV_OK || check_token_shape(1, n_frames, f, d) != SHARPV_OK) return 0;
+    return carve_tok_workspace(nullptr, n_frames, f, d).bytes;
+}
+
+int sharpv_prune_tokens(const void* feats, const int32_t* frame_offsets, int B, int n_frames, int f, int d,
+                        const sharpv_params* params, int32_t* out_idx, int32_t* out_counts, int32_t* out_offsets,
+                        void* out_feats, float* out_scores, float* out_ratio, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    int rc = check_params(params);
+    if (rc != SHARPV_OK) return rc;
+    if (feats == nullptr || out_idx == nullptr || out_counts == nullptr || out_offsets == nullptr ||
+        out_feats == nullptr)
+        return SHARPV_ERR_NULL;
+    rc = check_token_shape(B, n_frames, f, d);
+    if (rc != SHARPV_OK) return rc;
+    if (frame_offsets == nullptr && B != 1) return SHARPV_ERR_NULL;
+    if (params->min_keep > f) return SHARPV_ERR_PARAM;
+    if (!aligned(feats, 16) || !aligned(out_feats, 16) || !aligned(out_idx, 4) || !aligned(out_counts, 4) ||
+        !aligned(out_offsets, 4))
+        return SHARPV_ERR_SHAPE;
+    if (workspace == nullptr || !aligned(workspace, 256) ||
+        workspace_bytes < carve_tok_workspace(nullptr, n_frames, f, d).bytes)
+        return SHARPV_ERR_WORKSPACE;
+
+    TokArgs a;
+    a.feats = feats; a.frame_offsets = frame_offsets;
+    a.B = B; a.n = n_frames; a.f = f; a.d = d;
+    a.dtype = params->dtype; a.mode = params->mode; a.min_keep = params->min_keep;
+    a.w = params->w; a.K = params->K;
+    a.out_idx = out_idx; a.out_counts = out_counts; a.out_offsets = out_offsets;
+    a.out_feats = out_feats; a.out_scores = out_scores; a.out_ratio = out_ratio;
+    a.workspace = workspace; a.stream = (hipStream_t)stream;
+    return launch_prune_tokens(a);
+}
+
+size_t sharpv_prune_kv_workspace(int B, int S, int n_vis, const sharpv_params* params) {
+    if (check_params(params) != SHARPV_OK || check_kv_shape(B, S, n_vis, 8) != SHARPV_OK) return 0;
+    return carve_kv_workspace(nullptr, B, S, n_vis).bytes;
+}
+
+int sharpv_prune_kv(const void* hidden, const void* orig, const void* K, const void* V, int64_t kv_stride_h,
+                    int64_t kv_stride_s, const int32_t* seq_offsets, const int32_t* vis_start,
+                    const int32_t* vis_offsets, int B, int S, int vis_start0, int n_vis, int d, int H, int D,
+                    int layer, const sharpv_params* params, int32_t* out_idx, int32_t* out_count, void* K_out,
+                    void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    (void)layer;
+    int rc = check_params(params);
+    if (rc != SHARPV_OK) return rc;
+    if (hidden == nullptr || orig == nullptr || K == nullptr || V == nullptr || K_out == nullptr ||
+        V_out == nullptr || out_idx == nullptr || out_count == nullptr)
+        return SHARPV_ERR_NULL;
+    rc = check_kv_shape(B, S, n_vis, d);
+    if (rc != SHARPV_OK) return rc;
+    const bool ragged = seq_offsets != nullptr || vis_start != nullptr || vis_offsets != nullptr;
+    if (ragged && (seq_offsets == nullptr || vis_start == nullptr || vis_offsets == nullptr)) return SHARPV_ERR_NULL;
+    if (!ragged) {
+        if (B != 1) return SHARPV_ERR_NULL;
+        if (vis_start0 < 0 || (long long)vis_start0 + n_vis > S) return SHARPV_ERR_SHAPE;
+    }
+    const int64_t esz = params->dtype == SHARPV_F32 ? 4 : 2;
+    if (H < 1 || D < 1 || (D * esz) % 16 != 0) return SHARPV_ERR_SHAPE;
+    if (kv_stride_s < D || kv_stride_h < 1 || out_stride_h < D) return SHARPV_ERR_SHAPE;
+    if ((kv_stride_s * esz) % 16 != 0 || (kv_stride_h * esz) % 16 != 0 || (out_stride_h * esz) % 16 != 0)
+        return SHARPV_ERR_SHAPE;
+    if (!aligned(hidden, 16) || !aligned(orig, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(K_out, 16) ||
+        !aligned(V_out, 16) || !aligned(out_idx, 4) || !aligned(out_count, 4))
+        return SHARPV_ERR_SHAPE;
+    if (K_out == K || V_out == V || K_out == V || V_out == K) return SHARPV_ERR_SHAPE;
+    if (workspace == nullptr || !aligned(workspace, 256) ||
+        workspace_bytes < carve_kv_workspace(nullptr, B, S, n_vis).bytes)
+        return SHARPV_ERR_WORKSPACE;
+
+    KvArgs a;
+    a.hidden = hidden; a.orig = orig; a.K = K; a.V = V;
+    a.kv_stride_h = kv_stride_h; a.kv_stride_s = kv_stride_s; a.out_stride_h = out_stride_h;
+    a.sd.seq_offsets = seq_offsets; a.sd.vis_start = vis_start; a.sd.vis_offsets = vis_offsets;
+    a.sd.B = B; a.sd.vis_start0 = vis_start0; a.sd.n_vis = n_vis;
+    a.B = B; a.S = S; a.n_vis = n_vis; a.d = d; a.H = H; a.D = D;
+    a.dtype = params->dtype; a.kv_mode = params->kv_mode; a.M = params->M;
+    a.out_idx = out_idx; a.out_count = out_count; a.K_out = K_out; a.V_out = V_out;
+    a.out_cos = out_cos; a.out_mean_cos = out_mean_cos;
+    a.workspace = workspace; a.stream = (hipStream_t)stream;
+    return launch_prune_kv(a);
+}
+
+int sharpv_timing_enable(int max_launches) {
+    timing_destroy();
+    if (max_launches < 1) return SHARPV_ERR_SHAPE;
+    TimingPool& t = g_timing;
+    t.start.resize((size_t)max_launches);
+    t.stop.resize((size_t)max_launches);
+    t.kernel.assign((size_t)max_launches, -1);
+    for (int i = 0; i < max_launches; ++i) {
+        if (hipEventCreate(&t.start[(size_t)i]) != hipSuccess || hipEventCreate(&t.stop[(size_t)i]) != hipSuccess) {
+            t.start.resize((size_t)i);
+            t.stop.resize((size_t)i);
+            timing_destroy();
+            return SHARPV_ERR_DEVICE;
+        }
+    }
+    t.enabled = true;
+    return SHARPV_OK;
+}
+
+int sharpv_timing_disable(void) {
+    timing_destroy();
+    return SHARPV_OK;
+}
+
+int sharpv_timing_read(const char* kernel_name, int* n_launches, double* total_ms) {
+    if (kernel_name == nullptr || n_launches == nullptr || total_ms == nullptr) return SHARPV_ERR_NULL;
+    int id = -1;
+    for (int k = 0; k < kNumKernels; ++k)
+        if (strcmp(kernel_name, kKernelNames[k]) == 0) id = k;
+    if (id < 0) return SHARPV_ERR_PARAM;
+    TimingPool& t = g_timing;
+    int cnt = 0;
+    double tot = 0.0;
+    for (size_t i = 0; i < t.used; ++i) {
+        if (t.kernel[i] != id) continue;
+        if (hipEventSynchronize(t.stop[i]) != hipSuccess) return SHARPV_ERR_DEVICE;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, t.start[i], t.stop[i]) != hipSuccess) return SHARPV_ERR_DEVICE;
+        tot += (double)ms;
+        ++cnt;
+    }
+    *n_launches = cnt;
+    *total_ms = tot;
+    return SHARPV_OK;
+}
+
+}  // extern "C"

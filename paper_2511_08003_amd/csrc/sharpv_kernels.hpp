@@ -1,0 +1,113 @@
+// Host-side plumbing shared by the translation units of libsharpv: validated argument packs,
+// workspace carving, and the optional per-kernel event timing.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/sharpv.h"
+#include "sharpv_device.hpp"
+
+namespace sharpv {
+
+constexpr int kGroup = 64;          // packed positions per workgroup in the intra-LLM stage
+
+// Packed-batch description of the intra-LLM stage (device arrays, or the scalar form when B == 1).
+struct SeqDesc {
+    const int32_t* seq_offsets;     // [B+1] or nullptr
+    const int32_t* vis_start;       // [B]
+    const int32_t* vis_offsets;     // [B+1]
+    int B;
+    int vis_start0;
+    int n_vis;
+};
+
+struct KvArgs {
+    const void* hidden; const void* orig; const void* K; const void* V;
+    int64_t kv_stride_h, kv_stride_s, out_stride_h;
+    SeqDesc sd;
+    int B, S, n_vis, d, H, D, dtype, kv_mode;
+    float M;
+    int32_t* out_idx; int32_t* out_count;
+    void* K_out; void* V_out;
+    float* out_cos; float* out_mean_cos;
+    void* workspace;
+    hipStream_t stream;
+};
+
+struct TokArgs {
+    const void* feats;
+    const int32_t* frame_offsets;   // device [B+1] or nullptr
+    int B, n, f, d, dtype, mode, min_keep;
+    float w, K;
+    int32_t* out_idx; int32_t* out_counts; int32_t* out_offsets;
+    void* out_feats;
+    float* out_scores; float* out_ratio;
+    void* workspace;
+    hipStream_t stream;
+};
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct KvWorkspace {
+    unsigned long long* group_mask;  // [n_groups]
+    int32_t* group_count;            // [n_groups]
+    int32_t* drop_seq;               // [B]
+    float* cosv;                     // [n_vis]
+    size_t bytes;
+};
+
+inline KvWorkspace carve_kv_workspace(void* base, int B, int S, int n_vis) {
+    const size_t n_groups = ((size_t)S + kGroup - 1) / kGroup;
+    char* p = (char*)base;
+    size_t off = 0;
+    KvWorkspace w;
+    w.group_mask = (unsigned long long*)(p + off);  off += align_up(n_groups * 8);
+    w.group_count = (int32_t*)(p + off);            off += align_up(n_groups * 4);
+    w.drop_seq = (int32_t*)(p + off);               off += align_up((size_t)B * 4);
+    w.cosv = (float*)(p + off);                     off += align_up((size_t)n_vis * 4);
+    w.bytes = off;
+    return w;
+}
+
+struct TokWorkspace {
+    float* mean;        // [n, d]   frame means (float32)
+    float* aa;          // [n*f]    x.x
+    float* am;          // [n*f]    x.mean
+    float* ab;          // [n*f]    x.x_prev
+    int32_t* local_idx; // [n*f]    kept rows of frame t at [t*f, t*f + count)
+    size_t bytes;
+};
+
+inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d) {
+    char* p = (char*)base;
+    size_t off = 0;
+    const size_t N = (size_t)n * f;
+    TokWorkspace w;
+    w.mean = (float*)(p + off);         off += align_up((size_t)n * d * 4);
+    w.aa = (float*)(p + off);           off += align_up(N * 4);
+    w.am = (float*)(p + off);           off += align_up(N * 4);
+    w.ab = (float*)(p + off);           off += align_up(N * 4);
+    w.local_idx = (int32_t*)(p + off);  off += align_up(N * 4);
+    w.bytes = off;
+    return w;
+}
+
+// ---------------------------------------------------------------------------- event timing
+enum KernelId { kFrameMean = 0, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
+                kKvCosine, kKvMean, kKvGather, kNumKernels };
+
+void timing_begin(int kernel, hipStream_t st);
+void timing_end(int kernel, hipStream_t st);
+
+struct TimedLaunch {
+    int k; hipStream_t st;
+    TimedLaunch(int kernel, hipStream_t s) : k(kernel), st(s) { timing_begin(k, st); }
+    ~TimedLaunch() { timing_end(k, st); }
+};
+
+int launch_prune_tokens(const TokArgs& a);
+int launch_prune_kv(const KvArgs& a);
+
+}  // namespace sharpv

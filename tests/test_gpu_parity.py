@@ -1,0 +1,300 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracles on the same
+seeded inputs.
+
+Bars: kept counts, kept-index lists, compacted features / K / V, scores I, ratios and cosines are
+compared BIT-EXACTLY with the float32 canonical-order oracle (same precision, same order of
+roundings); scores and cosines are also compared with the float64 definition within 1e-3 relative
+(absolute floor 1e-4 where 2 - 2cos cancels near zero)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import canon, sharpv_ref as ref
+from paper_2511_08003_amd import sharpv, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-3, 1e-4
+
+
+def dev(a: np.ndarray, dtype: int) -> torch.Tensor:
+    if dtype == wl.BF16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda()
+
+
+def host(t: torch.Tensor, dtype: int) -> np.ndarray:
+    t = t.contiguous()
+    if dtype == wl.BF16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def i32(a) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, np.int32)).cuda()
+
+
+def run_tokens(feats: np.ndarray, dtype: int, frame_offsets, **over):
+    n, f, d = feats.shape
+    fo = None if frame_offsets is None or len(frame_offsets) == 2 else i32(frame_offsets)
+    got = sharpv.prune_tokens(dev(feats, dtype), fo, **over)
+    torch.cuda.synchronize()
+    return got
+
+
+def check_tokens(feats, dtype, frame_offsets, ref_frames=None, **over):
+    """Runs the GPU path and both oracles; returns the canonical-oracle result."""
+    n, f, d = feats.shape
+    offs = np.asarray([0, n] if frame_offsets is None else frame_offsets, np.int32)
+    kw = {k: over[k] for k in ("w", "mode", "K", "min_keep") if k in over}
+    got = run_tokens(feats, dtype, offs, **kw)
+    exp = canon.prune_tokens(feats, dtype, offs, **kw)
+    np.testing.assert_array_equal(got["counts"].cpu().numpy(), exp["counts"])
+    np.testing.assert_array_equal(got["offsets"].cpu().numpy(), exp["offsets"])
+    np.testing.assert_array_equal(got["idx"].cpu().numpy(), exp["idx"])
+    np.testing.assert_array_equal(host(got["out_feats"], dtype), exp["out_feats"])
+    np.testing.assert_array_equal(got["I"].cpu().numpy(), exp["I"])
+    np.testing.assert_array_equal(got["ratio"].cpu().numpy(), exp["ratio"])
+    # float64 definition on (a prefix of) the frames
+    m = n if ref_frames is None else min(n, ref_frames)
+    cut = [o for o in offs if o < m] + [m]
+    a = ref.prune_tokens(feats[:m], dtype, np.asarray(cut), **kw)
+    np.testing.assert_allclose(got["I"].cpu().numpy()[:m], a["I"], rtol=RTOL, atol=ATOL)
+    np.testing.assert_allclose(got["ratio"].cpu().numpy()[:m], a["ratio"], rtol=RTOL, atol=ATOL)
+    return exp
+
+
+def run_kv(hidden, orig, K, V, dtype, lay: wl.KVLayout, ragged=None, mean_cos=False, **over):
+    ragged = lay.B > 1 if ragged is None else ragged
+    kw = dict(over)
+    if ragged:
+        kw.update(seq_offsets=i32(lay.seq_offsets), vis_start=i32(lay.vis_start), vis_offsets=i32(lay.vis_offsets))
+    else:
+        kw.update(vis_start0=int(lay.vis_start[0]))
+    got = sharpv.prune_kv(dev(hidden, dtype), dev(orig, dtype), dev(K, dtype), dev(V, dtype), mean_cos=mean_cos,
+                          n_vis=lay.n_vis, **kw)
+    torch.cuda.synchronize()
+    return got
+
+
+def check_kv(hidden, orig, K, V, dtype, lay, ragged=None, **over):
+    kw = {k: over[k] for k in ("M", "kv_mode") if k in over}
+    got = run_kv(hidden, orig, K, V, dtype, lay, ragged=ragged, mean_cos=True, **kw)
+    args = (hidden, orig, K, V, dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets)
+    exp = canon.prune_kv(*args, **kw)
+    np.testing.assert_array_equal(got["counts"].cpu().numpy(), exp["counts"])
+    np.testing.assert_array_equal(got["idx"].cpu().numpy(), exp["idx"])
+    np.testing.assert_array_equal(got["cos"].cpu().numpy(), exp["cos"][:lay.n_vis])
+    np.testing.assert_array_equal(got["mean_cos"].cpu().numpy(), exp["mean_cos"])
+    np.testing.assert_array_equal(host(got["K_out"], dtype), exp["K_out"])
+    np.testing.assert_array_equal(host(got["V_out"], dtype), exp["V_out"])
+    a = ref.prune_kv(hidden, orig, K, V, dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets, **kw)
+    np.testing.assert_allclose(got["cos"].cpu().numpy(), a["cos"], rtol=RTOL, atol=ATOL)
+    return exp
+
+
+# ----------------------------------------------------------------------------- the five configurations
+@pytest.fixture(scope="module")
+def workloads():
+    cache = {}
+
+    def get(i):
+        if i not in cache:
+            cfg = wl.config(i)
+            cache.clear()                       # one big workload at a time
+            cache[i] = (cfg, wl.tokens_for(cfg, threads=8))
+        return cache[i]
+    return get
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+def test_prune_tokens_on_config(workloads, index):
+    cfg, tok = workloads(index)
+    print(f"config {index}: {cfg.name} frames={tok.n_total} f={cfg.f} d={cfg.d}", flush=True)
+    exp = check_tokens(tok.feats, cfg.dtype, tok.frame_offsets, ref_frames=48)
+    vr = exp["counts"].sum() / (tok.n_total * cfg.f)
+    assert 0.02 < vr < 0.9
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+def test_prune_kv_on_config(workloads, index):
+    cfg, tok = workloads(index)
+    lay = wl.kv_layout_for(cfg)
+    orig = tok.feats.reshape(-1, cfg.d)
+    orig32 = wl.storage_to_f32(tok.feats, tok.dtype).reshape(-1, cfg.d)
+    layers = cfg.kv_layers if index != 5 else (0, 9, 20)
+    for layer in layers:
+        print(f"config {index} layer {layer}: S={lay.S} n_vis={lay.n_vis}", flush=True)
+        kv = wl.kv_layer_for(cfg, tok, layer, threads=8, orig32=orig32)
+        exp = check_kv(kv["hidden"], orig, kv["K"], kv["V"], cfg.dtype, lay)
+        if layer == 0 and cfg.drift == "layer":
+            assert len(exp["idx"]) == lay.S          # decoder input: nothing degraded yet
+
+
+# ----------------------------------------------------------------------------- shapes and edge cases, stage 1
+def small_video(seed, n, f, d, dtype, rho=0.8, cuts=()):
+    spec = wl.VideoSpec(n=n, rho=np.full(n, rho), cuts=tuple(cuts), seed=seed)
+    return wl.make_tokens([spec], f, d, dtype, threads=2)
+
+
+@pytest.mark.parametrize("n,f,d,dtype", [
+    (1, 196, 3584, wl.BF16),      # a single frame: only the first-frame rule
+    (3, 1, 64, wl.BF16),          # one token per frame
+    (2, 1024, 64, wl.BF16),       # the largest frame
+    (5, 144, 4096, wl.BF16),      # PLLaVA-7B shape (Table 2)
+    (6, 196, 896, wl.BF16),       # LLaVA-OV-0.5B shape (Table 2): ragged last block
+    (4, 33, 8, wl.F32),           # a single chunk per row
+    (4, 65, 264, wl.F32),         # one block + one chunk
+    (7, 100, 520, wl.BF16),
+    (40, 50, 1024, wl.F32),
+])
+def test_prune_tokens_shapes(n, f, d, dtype):
+    tok = small_video(500 + n * 7 + f, n, f, d, dtype, cuts=(n // 2,) if n > 2 else ())
+    check_tokens(tok.feats, dtype, None)
+
+
+def test_prune_tokens_hyper_parameters():
+    tok = small_video(601, 6, 128, 768, wl.BF16, rho=0.6)
+    for w in (0.0, 0.5, 3.0):
+        check_tokens(tok.feats, wl.BF16, None, w=w)
+    check_tokens(tok.feats, wl.BF16, None, min_keep=100)
+    check_tokens(tok.feats, wl.BF16, None, min_keep=128)
+    for K in (0.5, 1.2, 1.6, 9.0):
+        check_tokens(tok.feats, wl.BF16, None, mode=1, K=K)
+
+
+def test_prune_tokens_static_negated_tied_and_ragged():
+    rng = np.random.default_rng(602)
+    f, d = 64, 512
+    F = wl.f32_to_bf16_bits(rng.standard_normal((f, d)).astype(np.float32))
+    G = wl.f32_to_bf16_bits(rng.standard_normal((f, d)).astype(np.float32))
+    neg = F ^ np.uint16(0x8000)
+    feats = np.stack([F, F, neg, neg, G, G, F])
+    exp = check_tokens(feats, wl.BF16, None)
+    assert exp["counts"][1] == 0 and exp["counts"][2] == f and exp["counts"][3] == 0
+    # every video one frame; and a few ragged splits of the same frames
+    check_tokens(feats, wl.BF16, np.arange(8))
+    check_tokens(feats, wl.BF16, [0, 2, 3, 7])
+    check_tokens(feats, wl.BF16, [0, 6, 7])
+    # exact ties inside a frame: slots i and i+32 identical in every frame
+    half = wl.f32_to_bf16_bits(rng.standard_normal((3, f // 2, d)).astype(np.float32))
+    tied = np.concatenate([half, half], axis=1)
+    exp = check_tokens(tied, wl.BF16, None, min_keep=21)
+    np.testing.assert_array_equal(exp["I"][:, :32], exp["I"][:, 32:])
+    # everything static: nothing survives, outputs stay empty
+    exp = check_tokens(np.stack([F, F, F])[1:], wl.BF16, None, w=0.0, mode=1, K=0.5)
+    assert exp["counts"][1] == 0
+
+
+def test_prune_tokens_is_deterministic():
+    tok = small_video(603, 12, 196, 1152, wl.F32)
+    x = dev(tok.feats, wl.F32)
+    runs = []
+    for _ in range(3):
+        g = sharpv.prune_tokens(x)
+        torch.cuda.synchronize()
+        runs.append((g["idx"].cpu().numpy().copy(), g["I"].cpu().numpy().copy(), host(g["out_feats"], wl.F32).copy()))
+    for r in runs[1:]:
+        for a, b in zip(runs[0], r):
+            np.testing.assert_array_equal(a, b)
+
+
+# ----------------------------------------------------------------------------- shapes and edge cases, stage 2
+def kv_case(seed, n_vis_per_seq, tb, ta, d, H, D, dtype, sigma_max=8.0):
+    rng = np.random.default_rng(seed)
+    lay = wl.make_kv_layout(n_vis_per_seq, tb, ta, H, D)
+    orig32 = rng.standard_normal((lay.n_vis, d)).astype(np.float32)
+    orig = wl.to_storage(orig32, dtype)
+    orig32 = wl.storage_to_f32(orig, dtype)
+    hidden32 = rng.standard_normal((lay.S, d)).astype(np.float32)
+    sig = (sigma_max * rng.random(lay.n_vis)).astype(np.float32)
+    pos = lay.visual_positions()
+    if lay.n_vis:
+        hidden32[pos] = orig32 + sig[:, None] * hidden32[pos]
+    hidden = wl.to_storage(hidden32, dtype)
+    K = wl.to_storage(rng.standard_normal((H, lay.S, D)).astype(np.float32), dtype)
+    V = wl.to_storage(rng.standard_normal((H, lay.S, D)).astype(np.float32), dtype)
+    return lay, hidden, orig, K, V
+
+
+@pytest.mark.parametrize("nvs,tb,ta,d,H,D,dtype", [
+    ([100], 0, 0, 512, 2, 64, wl.BF16),          # only visual tokens
+    ([1], 5, 3, 64, 1, 8, wl.BF16),              # one visual token, 16-byte K rows
+    ([63], 1, 0, 264, 4, 128, wl.F32),           # exactly one group of 64 positions
+    ([64], 1, 0, 896, 4, 128, wl.BF16),          # spills into a second group by one
+    ([300, 5, 77], 7, 9, 1152, 2, 32, wl.F32),   # ragged batch
+    ([130, 131], 0, 3, 4096, 8, 128, wl.BF16),
+])
+def test_prune_kv_shapes(nvs, tb, ta, d, H, D, dtype):
+    lay, hidden, orig, K, V = kv_case(700 + len(nvs) + d, nvs, tb, ta, d, H, D, dtype)
+    check_kv(hidden, orig, K, V, dtype, lay)
+    if lay.B == 1:
+        check_kv(hidden, orig, K, V, dtype, lay, ragged=True)      # the array form of a single sequence
+
+
+def test_prune_kv_thresholds_and_layer_mean_mode():
+    lay, hidden, orig, K, V = kv_case(710, [200, 90], 4, 6, 768, 2, 64, wl.BF16)
+    kept = []
+    for M in (-1.0, 0.0, 0.2, 0.5, 0.99, 1.5):
+        kept.append(len(check_kv(hidden, orig, K, V, wl.BF16, lay, M=M)["idx"]))
+    assert kept[0] == lay.S and kept[-1] == lay.S - lay.n_vis
+    assert all(b <= a for a, b in zip(kept, kept[1:]))
+    for M in (0.05, 0.3, 0.9):
+        check_kv(hidden, orig, K, V, wl.BF16, lay, M=M, kv_mode=1)
+
+
+def test_prune_kv_identity_negation_and_no_visual_tokens():
+    lay, hidden, orig, K, V = kv_case(711, [128], 3, 5, 512, 2, 64, wl.BF16)
+    pos = lay.visual_positions()
+    hidden[pos] = orig
+    exp = check_kv(hidden, orig, K, V, wl.BF16, lay)
+    assert len(exp["idx"]) == lay.S and np.all(exp["cos"] == 1.0)
+    hidden[pos] = orig ^ np.uint16(0x8000)
+    exp = check_kv(hidden, orig, K, V, wl.BF16, lay)
+    assert len(exp["idx"]) == 8 and np.all(exp["cos"] == -1.0)
+    hidden[pos[:5]] = 0                                             # zero rows: cosine 0 by convention
+    exp = check_kv(hidden, orig, K, V, wl.BF16, lay)
+    assert np.all(exp["cos"][:5] == 0.0)
+    lay0, h0, o0, K0, V0 = kv_case(712, [0], 6, 4, 64, 1, 8, wl.BF16)
+    got = run_kv(h0, np.zeros((1, 64), np.uint16), K0, V0, wl.BF16, lay0)
+    np.testing.assert_array_equal(got["idx"].cpu().numpy(), np.arange(10))
+    np.testing.assert_array_equal(host(got["K_out"], wl.BF16), K0)
+
+
+def test_prune_kv_strided_cache():
+    """K/V stored [S, H, D] and passed as a permuted [H, S, D] view (head stride D, position stride H*D)."""
+    lay, hidden, orig, K, V = kv_case(713, [150], 2, 2, 512, 4, 64, wl.BF16)
+    Kd = dev(K, wl.BF16).permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    Vd = dev(V, wl.BF16).permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    assert Kd.stride() == (64, 256, 1)
+    got = sharpv.prune_kv(dev(hidden, wl.BF16), dev(orig, wl.BF16), Kd, Vd, vis_start0=2)
+    torch.cuda.synchronize()
+    exp = canon.prune_kv(hidden, orig, K, V, wl.BF16, lay.seq_offsets, lay.vis_start, lay.vis_offsets)
+    np.testing.assert_array_equal(got["idx"].cpu().numpy(), exp["idx"])
+    np.testing.assert_array_equal(host(got["K_out"], wl.BF16), exp["K_out"])
+    np.testing.assert_array_equal(host(got["V_out"], wl.BF16), exp["V_out"])
+
+
+def test_prune_kv_is_deterministic():
+    lay, hidden, orig, K, V = kv_case(714, [500], 8, 8, 3584, 4, 128, wl.BF16)
+    args = [dev(hidden, wl.BF16), dev(orig, wl.BF16), dev(K, wl.BF16), dev(V, wl.BF16)]
+    outs = []
+    for _ in range(3):
+        g = sharpv.prune_kv(*args, vis_start0=8)
+        torch.cuda.synchronize()
+        outs.append((g["idx"].cpu().numpy().copy(), g["cos"].cpu().numpy().copy(), host(g["K_out"], wl.BF16).copy()))
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_error_codes_with_real_buffers():
+    x = torch.zeros((2, 16, 64), dtype=torch.bfloat16, device="cuda")
+    p = sharpv.default_params()
+    plan = sharpv.TokensPlan(2, 16, 64, p)
+    plan.workspace_bytes = 8
+    assert plan.run(x) == 5
+    p2 = sharpv.default_params(); p2.min_keep = 99
+    plan2 = sharpv.TokensPlan(2, 16, 64, sharpv.default_params())
+    plan2.params = p2
+    assert plan2.run(x) == 4

@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the SharpV pruning hot path on one MI355X.
+
+A step is one pass of the whole path over the long-video workload (256 frames x 196 tokens,
+d=3584 bf16): `sharpv_prune_tokens` once (score + select + compact), then `sharpv_prune_kv` on
+every layer of the 28-layer cache (cosine + decision + K/V gather).  Inputs are synthetic, seeded
+and resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is visual tokens per second through score+select+compact (the
+pre-LLM stage, timed inside the steps with events on the launch stream); `kv_prune` carries the
+intra-LLM stage's GB/s per layer call against the HBM peak; `roofline` describes the kernel that
+takes most of the step (kv_cosine), its duration measured with HIP events around every launch;
+`cpu_baseline` is the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = the 256-frame video)")
+    ap.add_argument("--layers", type=int, default=0, help="KV layers per step (0 = all layers of the config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1), help="input generator threads")
+    return ap.parse_args()
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path has no collectives between GPUs)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2511_08003_amd import sharpv, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    sharpv.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = wl.config(args.config)
+    esz = wl.elem_bytes(cfg.dtype)
+    tdt = torch.bfloat16 if cfg.dtype == wl.BF16 else torch.float32
+
+    def to_dev(a):
+        if cfg.dtype == wl.BF16:
+            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+
+    # ------------------------------------------------------------------ inputs (seeded, synthetic)
+    t0 = time.time()
+    tok = wl.tokens_for(cfg, threads=args.threads)
+    lay = wl.kv_layout_for(cfg)
+    n, f, d = tok.n_total, cfg.f, cfg.d
+    Nv, S = n * f, lay.S
+    feats = to_dev(tok.feats)
+    orig = feats.view(Nv, d)
+    orig32 = wl.storage_to_f32(tok.feats, tok.dtype).reshape(-1, d)
+    layers = list(range(cfg.n_layers)) if args.layers <= 0 else list(range(min(args.layers, cfg.n_layers)))
+    hidden, Kc, Vc = [], [], []
+    host_layer0 = None
+    for l in layers:
+        kv = wl.kv_layer_for(cfg, tok, l, threads=args.threads, orig32=orig32)
+        hidden.append(to_dev(kv["hidden"]))
+        Kc.append(to_dev(kv["K"]))
+        Vc.append(to_dev(kv["V"]))
+        if l == layers[len(layers) // 2]:
+            host_layer0 = (l, kv)
+    del orig32
+    ragged = lay.B > 1
+    fo = torch.from_numpy(tok.frame_offsets).to(dev) if tok.B > 1 else None
+    so = torch.from_numpy(lay.seq_offsets).to(dev) if ragged else None
+    vs = torch.from_numpy(lay.vis_start).to(dev) if ragged else None
+    vo = torch.from_numpy(lay.vis_offsets).to(dev) if ragged else None
+    gen_s = time.time() - t0
+
+    ptok = sharpv.default_params(cfg.dtype)
+    tplan = sharpv.TokensPlan(n, f, d, ptok, device=dev, scores=False, ratio=False)
+    kplan = sharpv.KvPlan(lay.B, S, lay.n_vis, d, cfg.H, cfg.D, ptok, device=dev, cos=False, mean_cos=False)
+    kept_per_layer = torch.zeros(len(layers), dtype=torch.int64, device=dev)
+
+    def stage1():
+        rc = tplan.run(feats, fo)
+        if rc:
+            raise RuntimeError(sharpv.status_string(rc))
+
+    def stage2(i):
+        rc = kplan.run(hidden[i], orig, Kc[i], Vc[i], int(lay.vis_start[0]), so, vs, vo, layers[i])
+        if rc:
+            raise RuntimeError(sharpv.status_string(rc))
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        stage1()
+        if ev:
+            ev[1].record()
+        for i in range(len(layers)):
+            stage2(i)
+        if ev:
+            ev[2].record()
+
+    # kept counts (for the algorithmic byte counts), outside the timed region
+    stage1()
+    torch.cuda.synchronize()
+    kept_tokens = int(tplan.out_offsets[-1].item())
+    for i in range(len(layers)):
+        stage2(i)
+        kept_per_layer[i] = kplan.out_count.sum()
+    torch.cuda.synchronize()
+    kept_kv = kept_per_layer.cpu().numpy().astype(np.int64)
+
+    # ------------------------------------------------------------------ timed region
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    ms_per_step = wall_ms / args.steps
+    ms_stage1 = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    ms_stage2 = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    ms_stage2_layer = ms_stage2 / len(layers)
+
+    # ------------------------------------------------------------------ per-kernel durations (events around every launch)
+    launches_per_step = 5 + 2 * len(layers)
+    sharpv.timing_enable(launches_per_step * args.steps + 8)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    kern = {}
+    for name in sharpv.KERNEL_NAMES:
+        cnt, ms = sharpv.timing_read(name)
+        if cnt:
+            kern[name] = {"launches": cnt, "avg_us": round(ms / cnt * 1e3, 3)}
+    sharpv.timing_disable()
+
+    # ------------------------------------------------------------------ algorithmic bytes (per launch / per call)
+    row = d * esz
+    bytes_stage1 = Nv * row + kept_tokens * row + 4 * kept_tokens + 8 * n
+    kv_row = cfg.H * cfg.D * esz
+    bytes_cos = 2 * lay.n_vis * row                                   # hidden + original rows of the visual tokens
+    bytes_gather_avg = float(np.mean(4 * kept_kv * kv_row + 4 * kept_kv))   # read + write kept K and V rows, indices
+    bytes_stage2_avg = bytes_cos + bytes_gather_avg
+    gbps_stage1 = bytes_stage1 / (ms_stage1 * 1e-3) / 1e9
+    gbps_stage2 = bytes_stage2_avg / (ms_stage2_layer * 1e-3) / 1e9
+    tokens_per_s = Nv / (ms_stage1 * 1e-3)
+
+    dom = "kv_cosine"
+    dom_gbps = bytes_cos / (kern[dom]["avg_us"] * 1e-6) / 1e9
+    for name, b in (("kv_cosine", bytes_cos), ("kv_gather", bytes_gather_avg),
+                    ("frame_mean", Nv * row), ("token_dots", Nv * row), ("token_gather", 2 * kept_tokens * row)):
+        if name in kern:
+            kern[name]["alg_GBps"] = round(b / (kern[name]["avg_us"] * 1e-6) / 1e9, 1)
+
+    out = {
+        "metric": "visual tokens/sec through score+select+compact; KV-prune GB/s vs HBM peak",
+        "value": round(tokens_per_s, 1),
+        "unit": "visual tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == wl.F32 else "bf16 inputs, f32 accumulation",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "frames": n, "tokens_per_frame": f, "d": d, "visual_tokens": Nv,
+                   "kv_layers_per_step": len(layers), "kv_heads": cfg.H, "head_dim": cfg.D, "seq_len": S,
+                   "w": 1.0, "M": 0.2, "kept_tokens": kept_tokens,
+                   "kept_kv_positions_mean": round(float(kept_kv.mean()), 1)},
+        "stage1": {"ms": round(ms_stage1, 4), "alg_bytes": int(bytes_stage1), "GBps": round(gbps_stage1, 1),
+                   "frac_hbm_peak": round(gbps_stage1 / HBM_PEAK_GBPS, 4)},
+        "kv_prune": {"ms_per_layer": round(ms_stage2_layer, 4), "alg_bytes_per_layer": int(bytes_stage2_avg),
+                     "GBps": round(gbps_stage2, 1), "frac_hbm_peak": round(gbps_stage2 / HBM_PEAK_GBPS, 4)},
+        "tokens_per_s_whole_step": round(Nv / (ms_per_step * 1e-3), 1),
+        "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "alg_bytes_per_launch": int(bytes_cos), "avg_launch_us": kern[dom]["avg_us"]},
+        "kernels": kern,
+        "input_generation_s": round(gen_s, 1),
+    }
+
+    # ------------------------------------------------------------------ CPU oracle on this machine's cores
+    if not args.no_cpu_baseline:
+        from oracle import canon
+        canon.lib()
+        t0 = time.perf_counter()
+        canon.prune_tokens(tok.feats, cfg.dtype, tok.frame_offsets)
+        cpu_s1 = time.perf_counter() - t0
+        l0, kv0 = host_layer0
+        t0 = time.perf_counter()
+        ck = canon.prune_kv(kv0["hidden"], tok.feats.reshape(-1, d), kv0["K"], kv0["V"], cfg.dtype,
+                            lay.seq_offsets, lay.vis_start, lay.vis_offsets, M=0.2)
+        cpu_s2 = time.perf_counter() - t0
+        b2 = bytes_cos + 4 * len(ck["idx"]) * kv_row + 4 * len(ck["idx"])
+        out["cpu_baseline"] = {
+            "value": round(Nv / cpu_s1, 1), "unit": "visual tokens/s", "cores": canon.threads(), "kind": "oracle",
+            "sample": f"float32 canonical-order oracle (C, OpenMP): pre-LLM stage on all {n} frames of the workload "
+                      f"({cpu_s1:.2f} s); intra-LLM stage on layer {l0} ({cpu_s2:.2f} s)",
+            "kv_prune_GBps": round(b2 / cpu_s2 / 1e9, 3),
+        }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

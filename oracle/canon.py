@@ -33,6 +33,8 @@ def lib() -> C.CDLL:
         build(force=False)
         L = C.CDLL(_SO)
         fp, ip, vp = C.POINTER(C.c_float), C.POINTER(C.c_int32), C.c_void_p
+        L.sharpv_canon_threads.restype = C.c_int
+        L.sharpv_canon_threads.argtypes = []
         L.sharpv_canon_rowdot.restype = C.c_float
         L.sharpv_canon_rowdot.argtypes = [fp, fp, C.c_int]
         L.sharpv_canon_sum32.restype = C.c_float
@@ -63,6 +65,10 @@ def _ip(a: np.ndarray):
 
 def _vp(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def threads() -> int:
+    return int(lib().sharpv_canon_threads())
 
 
 def rowdot(x: np.ndarray, y: np.ndarray) -> float:

@@ -45,6 +45,18 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Number of threads the outer loops (frames; tokens) run on. */
+int sharpv_canon_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 enum { CANON_F32 = 0, CANON_BF16 = 1 };
 

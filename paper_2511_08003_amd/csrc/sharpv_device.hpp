@@ -72,16 +72,40 @@ __device__ __forceinline__ float chain8(const float (&x)[8], const float (&y)[8]
     return c;
 }
 
-// Halving tree over the 32 lanes of each half-wavefront.  Every lane of a half ends up with the
-// value the written order assigns to leaf 0 (float addition is commutative, so the butterfly
-// reproduces p[l] + p[l+s] exactly).
-__device__ __forceinline__ float tree32(float v) {
-    v = v + __shfl_xor(v, 16);
-    v = v + __shfl_xor(v, 8);
-    v = v + __shfl_xor(v, 4);
-    v = v + __shfl_xor(v, 2);
-    v = v + __shfl_xor(v, 1);
+// Lane l of a 16-lane row receives the value of lane (l + n) mod 16 of the same row (DPP row rotate).
+template <int N> __device__ __forceinline__ float row_rotate(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
+
+// Strides 8, 4, 2, 1 of the halving tree inside every 16-lane row.  After the stride-8 step the
+// row holds each partial twice (lanes l and l^8), after stride 4 four times, and so on, so a
+// rotation by s delivers the partner of stride s whichever way it turns.
+__device__ __forceinline__ float tree16_rows(float v) {
+    v = v + row_rotate<8>(v);
+    v = v + row_rotate<4>(v);
+    v = v + row_rotate<2>(v);
+    v = v + row_rotate<1>(v);
     return v;
+}
+
+// Halving tree over the 32 lanes of each half-wavefront (strides 16, 8, 4, 2, 1).  Every lane of
+// a half ends up with the value the written order assigns to leaf 0 (float addition is
+// commutative, so the butterfly reproduces p[l] + p[l+s] exactly).  The stride-16 step exchanges
+// the two 16-lane rows of a half with v_permlane16_swap.
+__device__ __forceinline__ float tree32(float v) {
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return tree16_rows(__uint_as_float(r[0]) + __uint_as_float(r[1]));
+}
+
+// Two trees for the price of one: v_permlane16_swap exchanges the odd 16-lane rows of its first
+// operand with the even rows of its second, giving {a.r0, b.r0, a.r2, b.r2} and {a.r1, b.r1, a.r3,
+// b.r3}; their sum carries a's stride-16 sums in rows 0 and 2 and b's in rows 1 and 3.  Result:
+// lanes 0-15 / 32-47 hold TREE32 of `a` (lower / upper half-wavefront), lanes 16-31 / 48-63 hold
+// TREE32 of `b`.
+__device__ __forceinline__ float tree32_pair(float a, float b) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return tree16_rows(__uint_as_float(r[0]) + __uint_as_float(r[1]));
 }
 
 __device__ __forceinline__ float lane_value(float v, int lane) {

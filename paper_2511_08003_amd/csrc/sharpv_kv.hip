@@ -32,20 +32,88 @@ __device__ __forceinline__ bool locate_visual(const SeqDesc& sd, int s, int* ori
     return rel >= 0 && rel < sd.vis_offsets[b + 1] - lo;
 }
 
+// Three inner products of one (hidden row, original row) pair by one wavefront, chunk index
+// c = 64*q + lane in sweep q, with all loads of the row issued before the arithmetic starts.
+// NS = number of sweeps (d <= 512*NS); FULL = every lane of every sweep holds a chunk (d == 512*NS).
+template <typename T, int NS, bool FULL>
+__device__ __forceinline__ float row_cosine(const T* __restrict__ hrow, const T* __restrict__ orow,
+                                            int nchunks, int lane) {
+    RawChunk<T> rh[NS], ro[NS];
+#pragma unroll
+    for (int q = 0; q < NS; ++q) {
+        const int c = q * 64 + lane;
+        if (FULL || c < nchunks) {
+            rh[q] = load_raw<T>(hrow + (size_t)c * kChunk);
+            ro[q] = load_raw<T>(orow + (size_t)c * kChunk);
+        } else {
+            rh[q] = zero_raw<T>();
+            ro[q] = zero_raw<T>();
+        }
+    }
+    float hh = 0.0f, oo = 0.0f, ho = 0.0f;
+#pragma unroll
+    for (int q = 0; q < NS; ++q) {
+        float h[8], o[8];
+        unpack(rh[q], h);
+        unpack(ro[q], o);
+        const float pair = tree32_pair(chain8(h, h), chain8(o, o));   // rows 0,2: h.h   rows 1,3: o.o
+        const float single = tree32(chain8(h, o));
+        const bool odd = FULL || (q * 64 + kBlockChunks < nchunks);    // does the sweep's second block exist
+        hh = hh + lane_value(pair, 0);
+        oo = oo + lane_value(pair, 16);
+        ho = ho + lane_value(single, 0);
+        if (odd) {
+            hh = hh + lane_value(pair, 32);
+            oo = oo + lane_value(pair, 48);
+            ho = ho + lane_value(single, 32);
+        }
+    }
+    return cos_from_dots(ho, hh, oo);
+}
+
+// Any d: sweeps in a loop (used when d > 4096).
 template <typename T>
-__global__ __launch_bounds__(256) void kv_cosine_kernel(const T* __restrict__ hidden, const T* __restrict__ orig,
-                                                        SeqDesc sd, int S, int d, float M,
-                                                        float* __restrict__ cos_out,       // [n_vis] or nullptr
-                                                        unsigned long long* __restrict__ group_mask,
-                                                        int32_t* __restrict__ group_count) {
+__device__ __forceinline__ float row_cosine_loop(const T* __restrict__ hrow, const T* __restrict__ orow,
+                                                 int nchunks, int lane) {
+    float hh = 0.0f, oo = 0.0f, ho = 0.0f;
+    for (int c0 = 0; c0 < nchunks; c0 += 64) {
+        const int c = c0 + lane;
+        float phh = 0.0f, poo = 0.0f, pho = 0.0f;
+        if (c < nchunks) {
+            float h[8], o[8];
+            unpack(load_raw<T>(hrow + (size_t)c * kChunk), h);
+            unpack(load_raw<T>(orow + (size_t)c * kChunk), o);
+            phh = chain8(h, h);
+            poo = chain8(o, o);
+            pho = chain8(h, o);
+        }
+        phh = tree32(phh);
+        poo = tree32(poo);
+        pho = tree32(pho);
+        const bool odd = c0 + kBlockChunks < nchunks;
+        hh = add_blocks(hh, phh, odd);
+        oo = add_blocks(oo, poo, odd);
+        ho = add_blocks(ho, pho, odd);
+    }
+    return cos_from_dots(ho, hh, oo);
+}
+
+constexpr int kCosWaves = 4;        // wavefronts per workgroup of kv_cosine
+
+template <typename T, int NS, bool FULL>
+__global__ __launch_bounds__(kCosWaves * 64) void kv_cosine_kernel(const T* __restrict__ hidden,
+                                                                   const T* __restrict__ orig, SeqDesc sd, int S, int d,
+                                                                   float M, float* __restrict__ cos_out,   // [n_vis] or nullptr
+                                                                   unsigned long long* __restrict__ group_mask,
+                                                                   int32_t* __restrict__ group_count) {
     __shared__ int keep_flag[kGroup];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int group = blockIdx.x;
     const int nchunks = d / kChunk;
 
-    for (int j = 0; j < kGroup / 4; ++j) {
-        const int slot = j * 4 + wave;
+    for (int j = 0; j < kGroup / kCosWaves; ++j) {
+        const int slot = j * kCosWaves + wave;
         const int s = group * kGroup + slot;
         int keep = 0;
         if (s < S) {
@@ -54,29 +122,9 @@ __global__ __launch_bounds__(256) void kv_cosine_kernel(const T* __restrict__ hi
             if (locate_visual(sd, s, &p, &b)) {
                 const T* hrow = hidden + (size_t)s * d;
                 const T* orow = orig + (size_t)p * d;
-                float hh = 0.0f, oo = 0.0f, ho = 0.0f;
-                for (int c0 = 0; c0 < nchunks; c0 += 64) {
-                    const int c = c0 + lane;
-                    float phh = 0.0f, poo = 0.0f, pho = 0.0f;
-                    if (c < nchunks) {
-                        const RawChunk<T> rh = load_raw<T>(hrow + (size_t)c * kChunk);
-                        const RawChunk<T> ro = load_raw<T>(orow + (size_t)c * kChunk);
-                        float h[8], o[8];
-                        unpack(rh, h);
-                        unpack(ro, o);
-                        phh = chain8(h, h);
-                        poo = chain8(o, o);
-                        pho = chain8(h, o);
-                    }
-                    phh = tree32(phh);
-                    poo = tree32(poo);
-                    pho = tree32(pho);
-                    const bool odd = c0 + kBlockChunks < nchunks;
-                    hh = add_blocks(hh, phh, odd);
-                    oo = add_blocks(oo, poo, odd);
-                    ho = add_blocks(ho, pho, odd);
-                }
-                const float c = cos_from_dots(ho, hh, oo);
+                float c;
+                if constexpr (NS > 0) c = row_cosine<T, NS, FULL>(hrow, orow, nchunks, lane);
+                else c = row_cosine_loop<T>(hrow, orow, nchunks, lane);
                 keep = !(c < M);                        // Eq.7: discard iff cos < M
                 if (lane == 0 && cos_out != nullptr) cos_out[p] = c;
             }
@@ -91,6 +139,31 @@ __global__ __launch_bounds__(256) void kv_cosine_kernel(const T* __restrict__ hi
             group_count[group] = __popcll(m);
         }
     }
+}
+
+template <typename T>
+static void launch_kv_cosine(const KvArgs& a, const KvWorkspace& ws, float* cos_dst, int n_groups) {
+    const int nchunks = a.d / kChunk;
+    const int ns = (nchunks + 63) / 64;
+    const bool full = nchunks == ns * 64;
+    const dim3 grid(n_groups), block(kCosWaves * 64);
+#define SHARPV_COS_CASE(NS_)                                                                                        \
+    case NS_:                                                                                                       \
+        if (full)                                                                                                   \
+            hipLaunchKernelGGL((kv_cosine_kernel<T, NS_, true>), grid, block, 0, a.stream, (const T*)a.hidden,      \
+                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);     \
+        else                                                                                                        \
+            hipLaunchKernelGGL((kv_cosine_kernel<T, NS_, false>), grid, block, 0, a.stream, (const T*)a.hidden,     \
+                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);     \
+        break;
+    switch (ns) {
+        SHARPV_COS_CASE(1) SHARPV_COS_CASE(2) SHARPV_COS_CASE(3) SHARPV_COS_CASE(4)
+        SHARPV_COS_CASE(5) SHARPV_COS_CASE(6) SHARPV_COS_CASE(7) SHARPV_COS_CASE(8)
+        default:
+            hipLaunchKernelGGL((kv_cosine_kernel<T, 0, false>), grid, block, 0, a.stream, (const T*)a.hidden,
+                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);
+    }
+#undef SHARPV_COS_CASE
 }
 
 // Mean cosine of each sequence's visual tokens: 32 interleaved partial sums (token i goes to partial
@@ -199,21 +272,41 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__
     __syncthreads();
     if (K == nullptr) return;
 
-    // copy units of 16 bytes: (kept row r, tensor K|V, head h, 16-byte piece q)
+    // Copy in units of 16 bytes.  One kept position owns per_pos = 2*H*pieces units (K then V, head
+    // by head); a wavefront takes one kept position at a time, lane -> unit, so the source position
+    // is uniform and the per-lane offsets are computed once, outside the loop.
     const int pieces = row_bytes / 16;
-    const int per_row = 2 * H * pieces;
-    const int total = cnt * per_row;
-    for (int u = threadIdx.x; u < total; u += blockDim.x) {
-        const int r = u / per_row;
-        int rem = u - r * per_row;
-        const int kv = rem / (H * pieces);
-        rem -= kv * H * pieces;
+    const int per_pos = 2 * H * pieces;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x >> 6;
+    for (int v0 = 0; v0 < per_pos; v0 += 64) {
+        const int v = v0 + lane;
+        const bool live = v < per_pos;
+        const int kv = live ? v / (H * pieces) : 0;
+        const int rem = live ? v - kv * H * pieces : 0;
         const int h = rem / pieces;
         const int q = rem - h * pieces;
-        const long long s = (long long)group * kGroup + src_slot[r];
-        const char* src = (kv ? V : K) + h * stride_h_bytes + s * stride_s_bytes + (long long)q * 16;
-        char* dst = (kv ? V_out : K_out) + h * out_stride_h_bytes + (long long)(base + r) * row_bytes + (long long)q * 16;
-        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+        const char* src0 = (kv ? V : K) + h * stride_h_bytes + (long long)q * 16;
+        char* dst0 = (kv ? V_out : K_out) + h * out_stride_h_bytes + (long long)q * 16;
+        int r = wave;
+        for (; r + 3 * nwaves < cnt; r += 4 * nwaves) {           // four positions in flight per wavefront
+            uint4 t[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const long long s = (long long)group * kGroup + src_slot[r + k * nwaves];
+                if (live) t[k] = *reinterpret_cast<const uint4*>(src0 + s * stride_s_bytes);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (live) *reinterpret_cast<uint4*>(dst0 + (long long)(base + r + k * nwaves) * row_bytes) = t[k];
+        }
+        for (; r < cnt; r += nwaves) {
+            const long long s = (long long)group * kGroup + src_slot[r];
+            if (live)
+                *reinterpret_cast<uint4*>(dst0 + (long long)(base + r) * row_bytes) =
+                    *reinterpret_cast<const uint4*>(src0 + s * stride_s_bytes);
+        }
     }
 }
 
@@ -229,12 +322,8 @@ int launch_prune_kv(const KvArgs& a) {
 
     {
         TimedLaunch tl(kKvCosine, st);
-        if (a.dtype == SHARPV_BF16)
-            hipLaunchKernelGGL(kv_cosine_kernel<bf16_t>, dim3(n_groups), dim3(256), 0, st, (const bf16_t*)a.hidden,
-                               (const bf16_t*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);
-        else
-            hipLaunchKernelGGL(kv_cosine_kernel<float>, dim3(n_groups), dim3(256), 0, st, (const float*)a.hidden,
-                               (const float*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);
+        if (a.dtype == SHARPV_BF16) launch_kv_cosine<bf16_t>(a, ws, cos_dst, n_groups);
+        else launch_kv_cosine<float>(a, ws, cos_dst, n_groups);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
 

@@ -11,7 +11,8 @@
 
 namespace sharpv {
 
-constexpr int kGroup = 64;          // packed positions per workgroup in the intra-LLM stage
+constexpr int kGroup = 64;          // packed positions per 64-bit word of the keep mask
+constexpr int kMaskWord = 16;       // packed positions per 16-bit word of the keep mask (one workgroup each)
 
 // Packed-batch description of the intra-LLM stage (device arrays, or the scalar form when B == 1).
 struct SeqDesc {
@@ -51,8 +52,7 @@ struct TokArgs {
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct KvWorkspace {
-    unsigned long long* group_mask;  // [n_groups]
-    int32_t* group_count;            // [n_groups]
+    unsigned long long* group_mask;  // [n_groups] keep mask of 64 positions (written as 4 x 16 bits)
     int32_t* drop_seq;               // [B]
     float* cosv;                     // [n_vis]
     size_t bytes;
@@ -64,7 +64,6 @@ inline KvWorkspace carve_kv_workspace(void* base, int B, int S, int n_vis) {
     size_t off = 0;
     KvWorkspace w;
     w.group_mask = (unsigned long long*)(p + off);  off += align_up(n_groups * 8);
-    w.group_count = (int32_t*)(p + off);            off += align_up(n_groups * 4);
     w.drop_seq = (int32_t*)(p + off);               off += align_up((size_t)B * 4);
     w.cosv = (float*)(p + off);                     off += align_up((size_t)n_vis * 4);
     w.bytes = off;

@@ -2,15 +2,15 @@
 // embedding, keep/discard decision, and the gather of the layer's K/V rows into a compacted cache.
 //
 // Kernels
-//   kv_cosine   one wavefront per packed position; 64 positions per workgroup.  Streams the hidden
-//               row and the original row once (16-byte loads, 1 KB contiguous per wavefront and
-//               instruction), accumulates h.h, o.o, h.o in the fixed order of sharpv_device.hpp,
-//               decides Eq.7 and leaves a 64-bit keep mask and a kept count per workgroup.
+//   kv_cosine   one wavefront per packed position, 16 positions per workgroup.  A wavefront issues
+//               all 16-byte loads of its hidden row and original row at once (1 KB contiguous per
+//               instruction), accumulates h.h, o.o, h.o in the fixed order of sharpv_device.hpp and
+//               decides Eq.7; the workgroup leaves one 16-bit word of the keep mask.
 //   kv_mean     one workgroup per sequence: mean cosine of its visual tokens in a fixed order
 //               (only launched when the mean is asked for or decides, kv_mode 1).
-//   kv_gather   one workgroup per 64 positions: output offset = sum of the kept counts of the
-//               preceding groups, rank inside the group by popcount, then 16-byte copies of the
-//               kept K and V rows of every head.  A last workgroup writes the per-sequence counts.
+//   kv_gather   one workgroup per mask word (16 positions): output offset = popcount of the preceding
+//               mask words, rank inside the word by popcount, then batched 16-byte copies of the
+//               kept K and V rows, plane by plane.  A last workgroup writes the per-sequence counts.
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
@@ -98,70 +98,65 @@ __device__ __forceinline__ float row_cosine_loop(const T* __restrict__ hrow, con
     return cos_from_dots(ho, hh, oo);
 }
 
-constexpr int kCosWaves = 4;        // wavefronts per workgroup of kv_cosine
+constexpr int kCosRows = kMaskWord;  // packed positions (= wavefronts) per workgroup of kv_cosine
 
+// One wavefront per packed position, 16 positions per workgroup.  The 16 decisions of a workgroup
+// form one 16-bit word of the keep mask; four consecutive words are the 64-bit mask of a group of
+// kGroup = 64 positions (little endian: position 64g+i is bit i of 64-bit word g).
 template <typename T, int NS, bool FULL>
-__global__ __launch_bounds__(kCosWaves * 64) void kv_cosine_kernel(const T* __restrict__ hidden,
-                                                                   const T* __restrict__ orig, SeqDesc sd, int S, int d,
-                                                                   float M, float* __restrict__ cos_out,   // [n_vis] or nullptr
-                                                                   unsigned long long* __restrict__ group_mask,
-                                                                   int32_t* __restrict__ group_count) {
-    __shared__ int keep_flag[kGroup];
+__global__ __launch_bounds__(kCosRows * 64) void kv_cosine_kernel(const T* __restrict__ hidden,
+                                                                  const T* __restrict__ orig, SeqDesc sd, int S, int d,
+                                                                  float M, float* __restrict__ cos_out,   // [n_vis] or nullptr
+                                                                  uint16_t* __restrict__ mask16) {
+    __shared__ int keep_flag[kCosRows];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int group = blockIdx.x;
+    const int s = blockIdx.x * kCosRows + wave;
     const int nchunks = d / kChunk;
-
-    for (int j = 0; j < kGroup / kCosWaves; ++j) {
-        const int slot = j * kCosWaves + wave;
-        const int s = group * kGroup + slot;
-        int keep = 0;
-        if (s < S) {
-            keep = 1;                                   // system / instruction tokens are always kept
-            int p, b;
-            if (locate_visual(sd, s, &p, &b)) {
-                const T* hrow = hidden + (size_t)s * d;
-                const T* orow = orig + (size_t)p * d;
-                float c;
-                if constexpr (NS > 0) c = row_cosine<T, NS, FULL>(hrow, orow, nchunks, lane);
-                else c = row_cosine_loop<T>(hrow, orow, nchunks, lane);
-                keep = !(c < M);                        // Eq.7: discard iff cos < M
-                if (lane == 0 && cos_out != nullptr) cos_out[p] = c;
-            }
+    int keep = 0;
+    if (s < S) {
+        keep = 1;                                       // system / instruction tokens are always kept
+        int p, b;
+        if (locate_visual(sd, s, &p, &b)) {
+            const T* hrow = hidden + (size_t)s * d;
+            const T* orow = orig + (size_t)p * d;
+            float c;
+            if constexpr (NS > 0) c = row_cosine<T, NS, FULL>(hrow, orow, nchunks, lane);
+            else c = row_cosine_loop<T>(hrow, orow, nchunks, lane);
+            keep = !(c < M);                            // Eq.7: discard iff cos < M
+            if (lane == 0 && cos_out != nullptr) cos_out[p] = c;
         }
-        if (lane == 0) keep_flag[slot] = keep;
     }
+    if (lane == 0) keep_flag[wave] = keep;
     __syncthreads();
     if (wave == 0) {
-        const unsigned long long m = __ballot(keep_flag[lane] != 0);
-        if (lane == 0) {
-            group_mask[group] = m;
-            group_count[group] = __popcll(m);
-        }
+        const unsigned long long m = __ballot(lane < kCosRows && keep_flag[lane & (kCosRows - 1)] != 0);
+        if (lane == 0) mask16[blockIdx.x] = (uint16_t)m;
     }
 }
 
 template <typename T>
-static void launch_kv_cosine(const KvArgs& a, const KvWorkspace& ws, float* cos_dst, int n_groups) {
+static void launch_kv_cosine(const KvArgs& a, const KvWorkspace& ws, float* cos_dst) {
     const int nchunks = a.d / kChunk;
     const int ns = (nchunks + 63) / 64;
     const bool full = nchunks == ns * 64;
-    const dim3 grid(n_groups), block(kCosWaves * 64);
+    const dim3 grid((a.S + kCosRows - 1) / kCosRows), block(kCosRows * 64);
+    uint16_t* mask16 = reinterpret_cast<uint16_t*>(ws.group_mask);
 #define SHARPV_COS_CASE(NS_)                                                                                        \
     case NS_:                                                                                                       \
         if (full)                                                                                                   \
             hipLaunchKernelGGL((kv_cosine_kernel<T, NS_, true>), grid, block, 0, a.stream, (const T*)a.hidden,      \
-                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);     \
+                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, mask16);                             \
         else                                                                                                        \
             hipLaunchKernelGGL((kv_cosine_kernel<T, NS_, false>), grid, block, 0, a.stream, (const T*)a.hidden,     \
-                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);     \
+                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, mask16);                             \
         break;
     switch (ns) {
         SHARPV_COS_CASE(1) SHARPV_COS_CASE(2) SHARPV_COS_CASE(3) SHARPV_COS_CASE(4)
         SHARPV_COS_CASE(5) SHARPV_COS_CASE(6) SHARPV_COS_CASE(7) SHARPV_COS_CASE(8)
         default:
             hipLaunchKernelGGL((kv_cosine_kernel<T, 0, false>), grid, block, 0, a.stream, (const T*)a.hidden,
-                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, ws.group_mask, ws.group_count);
+                               (const T*)a.orig, a.sd, a.S, a.d, a.M, cos_dst, mask16);
     }
 #undef SHARPV_COS_CASE
 }
@@ -191,8 +186,7 @@ __global__ __launch_bounds__(64) void kv_mean_kernel(const float* __restrict__ c
 
 // kv_mode 1: rebuild the keep masks from the per-sequence decision.
 __global__ __launch_bounds__(64) void kv_mask_from_mean_kernel(SeqDesc sd, int S, const int32_t* __restrict__ drop_seq,
-                                                               unsigned long long* __restrict__ group_mask,
-                                                               int32_t* __restrict__ group_count) {
+                                                               unsigned long long* __restrict__ group_mask) {
     const int group = blockIdx.x;
     const int lane = threadIdx.x;
     const int s = group * kGroup + lane;
@@ -202,10 +196,7 @@ __global__ __launch_bounds__(64) void kv_mask_from_mean_kernel(SeqDesc sd, int S
         keep = locate_visual(sd, s, &p, &b) ? (drop_seq[b] == 0) : 1;
     }
     const unsigned long long m = __ballot(keep != 0);
-    if (lane == 0) {
-        group_mask[group] = m;
-        group_count[group] = __popcll(m);
-    }
+    if (lane == 0) group_mask[group] = m;
 }
 
 __device__ __forceinline__ int block_sum_int(int v, int* scratch) {
@@ -220,92 +211,94 @@ __device__ __forceinline__ int block_sum_int(int v, int* scratch) {
     return tot;
 }
 
-__device__ __forceinline__ int kept_before(const unsigned long long* group_mask, const int32_t* group_count,
-                                           int pos, int* scratch) {
-    // number of kept positions in [0, pos): whole groups by their counts, the rest by popcount
-    const int g = pos / kGroup;
+// Number of kept positions in [0, pos), pos <= S, from the 16-bit mask words.  Words wholly below pos
+// are complete (kv_cosine writes every word up to ceil(S/16) and clears the bits of positions >= S);
+// they are read four at a time as 64-bit words where all four lie below pos.
+__device__ __forceinline__ int kept_before(const uint16_t* __restrict__ mask16, int pos, int* scratch) {
+    const int w16 = pos / kMaskWord;             // complete 16-bit words below pos
+    const int w64 = w16 / 4;
+    const unsigned long long* m64 = reinterpret_cast<const unsigned long long*>(mask16);
     int part = 0;
-    for (int j = threadIdx.x; j < g; j += blockDim.x) part += group_count[j];
-    int tot = block_sum_int(part, scratch);
-    const int r = pos % kGroup;
-    if (r) tot += __popcll(group_mask[g] & ((1ull << r) - 1ull));
-    return tot;
+    for (int j = threadIdx.x; j < w64; j += blockDim.x) part += __popcll(m64[j]);
+    if (threadIdx.x == 0) {
+        for (int j = w64 * 4; j < w16; ++j) part += __popc((unsigned)mask16[j]);
+        const int r = pos % kMaskWord;
+        if (r) part += __popc((unsigned)mask16[w16] & ((1u << r) - 1u));
+    }
+    return block_sum_int(part, scratch);
 }
 
-__global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__ K, const char* __restrict__ V,
-                                                        long long stride_h_bytes, long long stride_s_bytes,
-                                                        char* __restrict__ K_out, char* __restrict__ V_out,
-                                                        long long out_stride_h_bytes, int row_bytes, int H,
-                                                        SeqDesc sd, int S, int n_groups,
-                                                        const unsigned long long* __restrict__ group_mask,
-                                                        const int32_t* __restrict__ group_count,
-                                                        int32_t* __restrict__ out_idx, int32_t* __restrict__ out_count) {
-    __shared__ int scratch[4];
-    __shared__ int src_slot[kGroup];
-    const int group = blockIdx.x;
+constexpr int kGatherThreads = 256;
+constexpr int kGatherBatch = 8;     // 16-byte loads in flight per lane
 
-    if (group == n_groups) {                     // extra workgroup: kept positions per sequence
+// One workgroup per mask word (16 packed positions).  Kept row r of the group goes to output row
+// base + r of every K / V head plane; lanes walk (r, 16-byte piece) so that one wavefront reads and
+// writes whole consecutive rows of one plane, and the planes are taken in batches with all loads of
+// a batch issued before its stores.
+__global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
+    const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
+    char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H,
+    SeqDesc sd, int S, int n_words, const uint16_t* __restrict__ mask16,
+    int32_t* __restrict__ out_idx, int32_t* __restrict__ out_count) {
+    __shared__ int scratch[kGatherThreads / 64];
+    __shared__ int src_slot[kMaskWord];
+    const int word = blockIdx.x;
+
+    if (word == n_words) {                       // extra workgroup: kept positions per sequence
         if (sd.seq_offsets == nullptr) {
-            const int tot = kept_before(group_mask, group_count, S, scratch);
+            const int tot = kept_before(mask16, S, scratch);
             if (threadIdx.x == 0) out_count[0] = tot;
         } else {
             for (int b = 0; b < sd.B; ++b) {
-                const int lo = kept_before(group_mask, group_count, sd.seq_offsets[b], scratch);
-                const int hi = kept_before(group_mask, group_count, sd.seq_offsets[b + 1], scratch);
+                const int lo = kept_before(mask16, sd.seq_offsets[b], scratch);
+                const int hi = kept_before(mask16, sd.seq_offsets[b + 1], scratch);
                 if (threadIdx.x == 0) out_count[b] = hi - lo;
             }
         }
         return;
     }
 
-    const int base = kept_before(group_mask, group_count, group * kGroup, scratch);
-    const unsigned long long mask = group_mask[group];
-    const int cnt = __popcll(mask);
-    if (threadIdx.x < kGroup) {
+    const unsigned mask = mask16[word];
+    if (mask == 0u) return;                      // nothing kept here (uniform over the workgroup)
+    const int base = kept_before(mask16, word * kMaskWord, scratch);
+    const int cnt = __popc(mask);
+    if (threadIdx.x < kMaskWord) {
         const int l = threadIdx.x;
-        if ((mask >> l) & 1ull) {
-            const int r = __popcll(mask & ((1ull << l) - 1ull));
+        if ((mask >> l) & 1u) {
+            const int r = __popc(mask & ((1u << l) - 1u));
             src_slot[r] = l;
-            out_idx[base + r] = group * kGroup + l;
+            out_idx[base + r] = word * kMaskWord + l;
         }
     }
     __syncthreads();
     if (K == nullptr) return;
 
-    // Copy in units of 16 bytes.  One kept position owns per_pos = 2*H*pieces units (K then V, head
-    // by head); a wavefront takes one kept position at a time, lane -> unit, so the source position
-    // is uniform and the per-lane offsets are computed once, outside the loop.
     const int pieces = row_bytes / 16;
-    const int per_pos = 2 * H * pieces;
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int nwaves = blockDim.x >> 6;
-    for (int v0 = 0; v0 < per_pos; v0 += 64) {
-        const int v = v0 + lane;
-        const bool live = v < per_pos;
-        const int kv = live ? v / (H * pieces) : 0;
-        const int rem = live ? v - kv * H * pieces : 0;
-        const int h = rem / pieces;
-        const int q = rem - h * pieces;
-        const char* src0 = (kv ? V : K) + h * stride_h_bytes + (long long)q * 16;
-        char* dst0 = (kv ? V_out : K_out) + h * out_stride_h_bytes + (long long)q * 16;
-        int r = wave;
-        for (; r + 3 * nwaves < cnt; r += 4 * nwaves) {           // four positions in flight per wavefront
-            uint4 t[4];
+    const int units = cnt * pieces;              // 16-byte units of one plane of this group
+    const int planes = 2 * H;                    // K heads, then V heads
+    for (int w = threadIdx.x; w < units; w += kGatherThreads) {
+        const int r = w / pieces;
+        const int q = w - r * pieces;
+        const long long src_off = ((long long)word * kMaskWord + src_slot[r]) * stride_s_bytes + (long long)q * 16;
+        const long long dst_off = (long long)(base + r) * row_bytes + (long long)q * 16;
+        for (int p0 = 0; p0 < planes; p0 += kGatherBatch) {
+            uint4 t[kGatherBatch];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const long long s = (long long)group * kGroup + src_slot[r + k * nwaves];
-                if (live) t[k] = *reinterpret_cast<const uint4*>(src0 + s * stride_s_bytes);
+            for (int k = 0; k < kGatherBatch; ++k) {
+                const int p = p0 + k;
+                if (p < planes) {
+                    const int h = p < H ? p : p - H;
+                    t[k] = *reinterpret_cast<const uint4*>((p < H ? K : V) + h * stride_h_bytes + src_off);
+                }
             }
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (live) *reinterpret_cast<uint4*>(dst0 + (long long)(base + r + k * nwaves) * row_bytes) = t[k];
-        }
-        for (; r < cnt; r += nwaves) {
-            const long long s = (long long)group * kGroup + src_slot[r];
-            if (live)
-                *reinterpret_cast<uint4*>(dst0 + (long long)(base + r) * row_bytes) =
-                    *reinterpret_cast<const uint4*>(src0 + s * stride_s_bytes);
+            for (int k = 0; k < kGatherBatch; ++k) {
+                const int p = p0 + k;
+                if (p < planes) {
+                    const int h = p < H ? p : p - H;
+                    *reinterpret_cast<uint4*>((p < H ? K_out : V_out) + h * out_stride_h_bytes + dst_off) = t[k];
+                }
+            }
         }
     }
 }
@@ -322,8 +315,8 @@ int launch_prune_kv(const KvArgs& a) {
 
     {
         TimedLaunch tl(kKvCosine, st);
-        if (a.dtype == SHARPV_BF16) launch_kv_cosine<bf16_t>(a, ws, cos_dst, n_groups);
-        else launch_kv_cosine<float>(a, ws, cos_dst, n_groups);
+        if (a.dtype == SHARPV_BF16) launch_kv_cosine<bf16_t>(a, ws, cos_dst);
+        else launch_kv_cosine<float>(a, ws, cos_dst);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
 
@@ -336,18 +329,19 @@ int launch_prune_kv(const KvArgs& a) {
         if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
         if (a.kv_mode == 1) {
             hipLaunchKernelGGL(kv_mask_from_mean_kernel, dim3(n_groups), dim3(64), 0, st, a.sd, a.S,
-                               (const int32_t*)ws.drop_seq, ws.group_mask, ws.group_count);
+                               (const int32_t*)ws.drop_seq, ws.group_mask);
             if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
         }
     }
 
     {
         TimedLaunch tl(kKvGather, st);
-        hipLaunchKernelGGL(kv_gather_kernel, dim3(n_groups + 1), dim3(256), 0, st, (const char*)a.K, (const char*)a.V,
-                           (long long)(a.kv_stride_h * (int64_t)esz), (long long)(a.kv_stride_s * (int64_t)esz),
-                           (char*)a.K_out, (char*)a.V_out, (long long)(a.out_stride_h * (int64_t)esz),
-                           (int)(a.D * esz), a.H, a.sd, a.S, n_groups, (const unsigned long long*)ws.group_mask,
-                           (const int32_t*)ws.group_count, a.out_idx, a.out_count);
+        const int n_words = (a.S + kMaskWord - 1) / kMaskWord;
+        hipLaunchKernelGGL(kv_gather_kernel, dim3(n_words + 1), dim3(kGatherThreads), 0, st, (const char*)a.K,
+                           (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),
+                           (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,
+                           (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, a.sd, a.S, n_words,
+                           reinterpret_cast<const uint16_t*>(ws.group_mask), a.out_idx, a.out_count);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
     return SHARPV_OK;

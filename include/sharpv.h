@@ -143,7 +143,7 @@ int sharpv_prune_kv(
  * taken from a pool of `max_launches` pairs (launches beyond the pool go untimed).
  * sharpv_timing_read synchronises on the recorded events and returns, for the kernel with the
  * given name, the number of timed launches and their summed duration in milliseconds.
- * Kernel names: "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
+ * Kernel names: "frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
  * "kv_cosine", "kv_mean", "kv_gather".  Not thread-safe; one device.
  */
 int sharpv_timing_enable(int max_launches);     /* creates the pool; resets earlier records */

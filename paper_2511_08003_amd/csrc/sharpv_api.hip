@@ -18,7 +18,7 @@ struct TimingPool {
     bool open = false;              // a begin without its end yet
 } g_timing;
 
-const char* const kKernelNames[kNumKernels] = {"frame_mean", "token_dots", "frame_select", "count_scan",
+const char* const kKernelNames[kNumKernels] = {"frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan",
                                                "token_gather", "kv_cosine", "kv_mean", "kv_gather"};
 }  // namespace
 
@@ -113,7 +113,7 @@ int sharpv_version(void) { return 100; }
 
 size_t sharpv_prune_tokens_workspace(int n_frames, int f, int d, const sharpv_params* params) {
     if (check_params(params) != SHARPV_OK || check_token_shape(1, n_frames, f, d) != SHARPV_OK) return 0;
-    return carve_tok_workspace(nullptr, n_frames, f, d).bytes;
+    return carve_tok_workspace(nullptr, n_frames, f, d, params->dtype).bytes;
 }
 
 int sharpv_prune_tokens(const void* feats, const int32_t* frame_offsets, int B, int n_frames, int f, int d,
@@ -133,7 +133,7 @@ int sharpv_prune_tokens(const void* feats, const int32_t* frame_offsets, int B, 
         !aligned(out_offsets, 4))
         return SHARPV_ERR_SHAPE;
     if (workspace == nullptr || !aligned(workspace, 256) ||
-        workspace_bytes < carve_tok_workspace(nullptr, n_frames, f, d).bytes)
+        workspace_bytes < carve_tok_workspace(nullptr, n_frames, f, d, params->dtype).bytes)
         return SHARPV_ERR_WORKSPACE;
 
     TokArgs a;

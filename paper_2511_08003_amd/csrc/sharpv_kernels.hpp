@@ -70,31 +70,42 @@ inline KvWorkspace carve_kv_workspace(void* base, int B, int S, int n_vis) {
     return w;
 }
 
+// The fused mean + inner-product kernel keeps three frame slabs in registers: bf16 rows only, and at
+// most 13 rows per thread (f <= 208).  Other shapes take the two-kernel path.
+inline bool tok_uses_slab(int dtype, int f) { return dtype == SHARPV_BF16 && f <= 208; }
+inline int tok_num_slabs(int d) { return (d + kBlockElems - 1) / kBlockElems; }
+
 struct TokWorkspace {
-    float* mean;        // [n, d]   frame means (float32)
-    float* aa;          // [n*f]    x.x
-    float* am;          // [n*f]    x.mean
-    float* ab;          // [n*f]    x.x_prev
-    int32_t* local_idx; // [n*f]    kept rows of frame t at [t*f, t*f + count)
+    float* mean;        // [n, d]            frame means (two-kernel path only)
+    float* aa;          // [nparts][n*f]     x.x       (per-slab shares on the fused path, nparts = slabs)
+    float* am;          // [nparts][n*f]     x.mean
+    float* ab;          // [nparts][n*f]     x.x_prev
+    float* part_mm;     // [n][slabs]        mean.mean shares (fused path only)
+    int32_t* local_idx; // [n*f]             kept rows of frame t at [t*f, t*f + count)
+    int nparts;
     size_t bytes;
 };
 
-inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d) {
+inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d, int dtype) {
     char* p = (char*)base;
     size_t off = 0;
     const size_t N = (size_t)n * f;
+    const bool slab = tok_uses_slab(dtype, f);
+    const int slabs = tok_num_slabs(d);
     TokWorkspace w;
-    w.mean = (float*)(p + off);         off += align_up((size_t)n * d * 4);
-    w.aa = (float*)(p + off);           off += align_up(N * 4);
-    w.am = (float*)(p + off);           off += align_up(N * 4);
-    w.ab = (float*)(p + off);           off += align_up(N * 4);
+    w.nparts = slab ? slabs : 1;
+    w.mean = (float*)(p + off);         off += slab ? 0 : align_up((size_t)n * d * 4);
+    w.aa = (float*)(p + off);           off += align_up((size_t)w.nparts * N * 4);
+    w.am = (float*)(p + off);           off += align_up((size_t)w.nparts * N * 4);
+    w.ab = (float*)(p + off);           off += align_up((size_t)w.nparts * N * 4);
+    w.part_mm = (float*)(p + off);      off += slab ? align_up((size_t)n * slabs * 4) : 0;
     w.local_idx = (int32_t*)(p + off);  off += align_up(N * 4);
     w.bytes = off;
     return w;
 }
 
 // ---------------------------------------------------------------------------- event timing
-enum KernelId { kFrameMean = 0, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
+enum KernelId { kFrameSlab = 0, kFrameMean, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
                 kKvCosine, kKvMean, kKvGather, kNumKernels };
 
 void timing_begin(int kernel, hipStream_t st);

@@ -2,7 +2,13 @@
 // scores, per-frame retention ratio and top-k, and the compaction of the token stream.
 //
 // Kernels
-//   frame_mean    workgroup = (frame, 256-column slab), 32 row classes x 32 lanes: row i goes to
+//   frame_slab    (bf16, f <= 208) fused first two steps with every feature read once: a workgroup owns
+//                 one 256-column slab (= one block of the summation order) and walks a run of consecutive
+//                 frames, holding the previous, the current and the next frame's slab in registers.  Per
+//                 frame: column sums by row class -> LDS -> halving tree -> slab of the frame mean; then
+//                 per row the slab's share of x.x, x.mean and x.x_prev (one tree per row and block).
+//                 The per-slab shares are summed in ascending slab order by frame_select.
+//   frame_mean    (other shapes) workgroup = (frame, 256-column slab), 32 row classes x 32 lanes: row i goes to
 //                 class i % 32, each class adds its rows in ascending order, the 32 classes are
 //                 reduced by a halving tree in LDS, divided by f.  Eq.2's average representation.
 //   token_dots    one wavefront per token row: x.x, x.mean_t and x.x_prev in the fixed order of
@@ -58,6 +64,161 @@ __global__ __launch_bounds__(1024) void frame_mean_kernel(const T* __restrict__ 
     }
 }
 
+// ---------------------------------------------------------------------------- fused mean + inner products
+constexpr int kSlabThreads = 512;   // 16 row groups x 32 lanes
+
+// Thread (g, l): lane l owns chunk l of the slab, row group g owns rows g, g+16, g+32, ... of a frame.
+// Row i belongs to class i % 32 of the column sum, i.e. class g for even k and class g+16 for odd k
+// (i = g + 16k).  KR = rows per thread, f <= 16*KR.  Loads use one uniform frame base plus 32-bit
+// byte offsets.
+template <int KR>
+__device__ __forceinline__ void load_slab(RawChunk<bf16_t> (&buf)[KR], const char* __restrict__ frame_base,
+                                          uint32_t lane_off, uint32_t row16_bytes, int f, int g, bool live) {
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+        const int i = g + 16 * k;
+        if (live && i < f)
+            buf[k].q = *reinterpret_cast<const uint4*>(frame_base + (lane_off + (uint32_t)k * row16_bytes));
+        else
+            buf[k] = zero_raw<bf16_t>();
+    }
+}
+
+// Makes the compiler forget what it knows about the packed registers, so that widened copies of a
+// whole frame slab (eight floats per chunk) are recomputed where needed instead of being kept live.
+template <int KR>
+__device__ __forceinline__ void forget_unpacked(RawChunk<bf16_t> (&buf)[KR]) {
+#pragma unroll
+    for (int k = 0; k < KR; ++k)
+        asm volatile("" : "+v"(buf[k].q.x), "+v"(buf[k].q.y), "+v"(buf[k].q.z), "+v"(buf[k].q.w));
+}
+
+// A workgroup owns slab `slab` (256 columns = one block of the summation order) of the frames
+// [t0, t1).  Two frame slabs live in registers: the current frame and the next one, whose loads are
+// in flight while the current frame is worked on.  For the current frame: column sums -> frame-mean
+// slab -> the slab's share of x.x and x.mean per row.  Then, with the next frame landed, its share of
+// x.x_prev (next frame's rows against the current ones).  The run starts one frame early (t0-1) for
+// that last product only.
+template <int KR>
+__global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* __restrict__ feats, int n, int f, int d,
+                                                                  int nslabs, int ranges,
+                                                                  float* __restrict__ part_aa,   // [nslabs][n*f]
+                                                                  float* __restrict__ part_am,
+                                                                  float* __restrict__ part_ab,
+                                                                  float* __restrict__ part_mm) { // [n][nslabs]
+    __shared__ float sm[16][kBlockElems];        // column sums of classes g and g+16 already added
+    __shared__ float smean[kBlockElems];
+    const int tid = threadIdx.x;
+    const int l = tid & 31;
+    const int g = tid >> 5;
+    const int slab = blockIdx.x % nslabs;
+    const int range = blockIdx.x / nslabs;
+    const int t0 = (int)((long long)range * n / ranges);
+    const int t1 = (int)((long long)(range + 1) * n / ranges);
+    if (t0 >= t1) return;
+    const int c = slab * kBlockChunks + l;
+    const bool live = c < d / kChunk;
+    const size_t N = (size_t)n * f;
+    float* const pa = part_aa + (size_t)slab * N;
+    float* const pm = part_am + (size_t)slab * N;
+    float* const pb = part_ab + (size_t)slab * N;
+    const size_t frame_bytes = (size_t)f * d * sizeof(bf16_t);
+    const uint32_t lane_off = (uint32_t)(((size_t)g * d + (size_t)c * kChunk) * sizeof(bf16_t));
+    const uint32_t row16_bytes = (uint32_t)(16u * (uint32_t)d * sizeof(bf16_t));
+    const char* const fbase = reinterpret_cast<const char*>(feats);
+    const bool lead = (l & 15) == 0;             // lanes 0 and 16 of each half hold the two results of a pair
+    const bool second = l != 0;
+
+    RawChunk<bf16_t> cur[KR], nxt[KR];
+    const int tb = t0 > 0 ? t0 - 1 : t0;
+    load_slab<KR>(cur, fbase + (size_t)tb * frame_bytes, lane_off, row16_bytes, f, g, live);
+
+    for (int t = tb; t < t1; ++t) {
+        const bool has_next = t + 1 < t1;
+        if (has_next) load_slab<KR>(nxt, fbase + (size_t)(t + 1) * frame_bytes, lane_off, row16_bytes, f, g, live);
+
+        if (t >= t0) {
+            // column sums: rows of class g (even k) and class g+16 (odd k), each ascending; the
+            // stride-16 level of the class tree adds the two right here
+            float pe[8], po[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { pe[j] = 0.0f; po[j] = 0.0f; }
+#pragma unroll
+            for (int k = 0; k < KR; ++k) {
+                float v[8];
+                unpack(cur[k], v);
+                if (k & 1) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) po[j] = po[j] + v[j];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) pe[j] = pe[j] + v[j];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sm[g][l * 8 + j] = pe[j] + po[j];
+            forget_unpacked<KR>(cur);
+            __syncthreads();
+            if (tid < kBlockElems) {             // one thread per column: strides 8, 4, 2, 1 over the 16 sums
+                float q[16];
+#pragma unroll
+                for (int gg = 0; gg < 16; ++gg) q[gg] = sm[gg][tid];
+#pragma unroll
+                for (int st = 8; st >= 1; st >>= 1)
+#pragma unroll
+                    for (int ll = 0; ll < st; ++ll) q[ll] = q[ll] + q[ll + st];
+                smean[tid] = q[0] / (float)f;
+            }
+            __syncthreads();
+            float m[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) m[j] = smean[l * 8 + j];
+            if (tid < 64) {                      // this slab's share of mean.mean
+                const float v = tree32(chain8(m, m));
+                if (tid == 0) part_mm[(size_t)t * nslabs + slab] = v;
+            }
+            const size_t row0 = (size_t)t * f;
+#pragma unroll
+            for (int k = 0; k < KR; ++k) {       // the slab's share of x.x (lanes 0-15) and x.mean (lanes 16-31)
+                const int i = g + 16 * k;
+                float a[8];
+                unpack(cur[k], a);
+                const float x = tree32_pair(chain8(a, a), chain8(a, m));
+                if (lead && i < f) (second ? pm : pa)[row0 + i] = x;
+                __builtin_amdgcn_sched_barrier(0);   // keep the rows' temporaries from piling up in registers
+            }
+        }
+
+        if (has_next) {                          // share of x.x_prev of frame t+1, two rows per tree
+            forget_unpacked<KR>(cur);
+            const size_t row1 = (size_t)(t + 1) * f;
+#pragma unroll
+            for (int k = 0; k < KR; k += 2) {
+                const int i0 = g + 16 * k;
+                float a[8], b[8];
+                unpack(nxt[k], a);
+                unpack(cur[k], b);
+                const float ab0 = chain8(a, b);
+                if (k + 1 < KR) {
+                    float a1[8], b1[8];
+                    unpack(nxt[k + 1], a1);
+                    unpack(cur[k + 1], b1);
+                    const float z = tree32_pair(ab0, chain8(a1, b1));
+                    const int iz = second ? i0 + 16 : i0;
+                    if (lead && iz < f) pb[row1 + iz] = z;
+                } else {
+                    const float z = tree32(ab0);
+                    if (l == 0 && i0 < f) pb[row1 + i0] = z;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int k = 0; k < KR; ++k) cur[k] = nxt[k];
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------- per-token inner products
 template <typename T>
 __global__ __launch_bounds__(256) void token_dots_kernel(const T* __restrict__ feats, const float* __restrict__ mean,
@@ -105,8 +266,11 @@ __global__ __launch_bounds__(256) void token_dots_kernel(const T* __restrict__ f
 }
 
 // ---------------------------------------------------------------------------- scores, ratio, top-k
-__global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restrict__ mean, const float* __restrict__ aa,
-                                                            const float* __restrict__ am, const float* __restrict__ ab,
+__global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restrict__ mean,      // [n][d] or nullptr
+                                                            const float* __restrict__ part_mm,   // [n][nparts] if mean == nullptr
+                                                            const float* __restrict__ aa, const float* __restrict__ am,
+                                                            const float* __restrict__ ab,        // each [nparts][n*f]
+                                                            int nparts, size_t part_stride,
                                                             const int32_t* __restrict__ frame_offsets, int B,
                                                             int f, int d, float w, int mode, float Kthr, int min_keep,
                                                             int32_t* __restrict__ local_idx,
@@ -129,8 +293,9 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
     const int nchunks = d / kChunk;
     const int nblocks = (nchunks + kBlockChunks - 1) / kBlockChunks;
 
-    // mean.mean in the common order: one half-wavefront per 256-element block
-    {
+    // mean.mean in the common order: one half-wavefront per 256-element block (or the per-slab
+    // shares left by the fused kernel)
+    if (mean != nullptr) {
         const float* m = mean + (size_t)t * d;
         const int half = tid >> 5, hl = tid & 31, nhalves = nthreads >> 5;
         for (int b0 = 0; b0 < nblocks; b0 += nhalves) {
@@ -145,6 +310,8 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
             v = tree32(v);
             if (hl == 0 && b < nblocks) sblk[b] = v;
         }
+    } else {
+        for (int b = tid; b < nblocks; b += nthreads) sblk[b] = part_mm[(size_t)t * nblocks + b];
     }
     if (tid == 0) s_first = (frame_offsets == nullptr) ? (t == 0) : 0;
     __syncthreads();
@@ -165,9 +332,24 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
     float score = 0.0f;
     if (i < f) {
         const size_t r = (size_t)t * f + i;
-        const float xx = aa[r];
-        const float S = dissim_from_dots(am[r], xx, mm);                     // Eq.2
-        const float T = first ? S : dissim_from_dots(ab[r], xx, aa[r - f]);  // Eq.3 (Eq.6 on a first frame)
+        // block shares added in ascending block order (a single share when the rows were summed whole)
+        float xx = 0.0f, xm = 0.0f, xp = 0.0f, pp = 0.0f;
+        if (nparts == 1) {
+            xx = aa[r]; xm = am[r];
+            if (!first) { xp = ab[r]; pp = aa[r - f]; }
+        } else {
+            for (int sb = 0; sb < nparts; ++sb) {
+                const size_t o = (size_t)sb * part_stride + r;
+                xx = xx + aa[o];
+                xm = xm + am[o];
+                if (!first) {
+                    xp = xp + ab[o];
+                    pp = pp + aa[o - f];
+                }
+            }
+        }
+        const float S = dissim_from_dots(xm, xx, mm);                        // Eq.2
+        const float T = first ? S : dissim_from_dots(xp, xx, pp);            // Eq.3 (Eq.6 on a first frame)
         score = __builtin_fmaf(w, S, T);                                     // Eq.4
         sI[i] = score;
         sTT[i] = T * T;
@@ -252,7 +434,7 @@ __global__ __launch_bounds__(1024) void count_scan_kernel(const int32_t* __restr
 }
 
 // ---------------------------------------------------------------------------- compaction
-constexpr int kGatherSplit = 4;     // workgroups per frame
+constexpr int kGatherSplit = 16;    // workgroups (of four wavefronts) per frame
 __global__ __launch_bounds__(256) void token_gather_kernel(const char* __restrict__ feats, int f, int row_bytes,
                                                            const int32_t* __restrict__ local_idx,
                                                            const int32_t* __restrict__ counts,
@@ -262,13 +444,22 @@ __global__ __launch_bounds__(256) void token_gather_kernel(const char* __restric
     const int lane = threadIdx.x & 63;
     const int q = blockIdx.y * 4 + (threadIdx.x >> 6);
     const int cnt = counts[t];
+    if (q >= cnt) return;
     const int off = offsets[t];
     const int units = row_bytes / 16;
-    for (int r = q; r < cnt; r += kGatherSplit * 4) {
+    for (int r = q; r < cnt; r += kGatherSplit * 4) {            // one wavefront per kept row
         const int src_row = local_idx[(size_t)t * f + r];
         const uint4* src = reinterpret_cast<const uint4*>(feats + (size_t)src_row * row_bytes);
         uint4* dst = reinterpret_cast<uint4*>(out_feats + (size_t)(off + r) * row_bytes);
-        for (int u = lane; u < units; u += 64) dst[u] = src[u];
+        for (int u0 = lane; u0 < units; u0 += 64 * 8) {          // eight 16-byte loads in flight per lane
+            uint4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (u0 + 64 * k < units) v[k] = src[u0 + 64 * k];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (u0 + 64 * k < units) dst[u0 + 64 * k] = v[k];
+        }
         if (lane == 0) out_idx[off + r] = src_row;
     }
 }
@@ -276,23 +467,36 @@ __global__ __launch_bounds__(256) void token_gather_kernel(const char* __restric
 // ---------------------------------------------------------------------------- host side
 int launch_prune_tokens(const TokArgs& a) {
     hipStream_t st = a.stream;
-    TokWorkspace ws = carve_tok_workspace(a.workspace, a.n, a.f, a.d);
+    TokWorkspace ws = carve_tok_workspace(a.workspace, a.n, a.f, a.d, a.dtype);
     const int n_rows = a.n * a.f;
-    const int slabs = (a.d + kBlockElems - 1) / kBlockElems;
+    const int slabs = tok_num_slabs(a.d);
     const size_t esz = a.dtype == SHARPV_F32 ? 4 : 2;
+    const bool fused = tok_uses_slab(a.dtype, a.f);
 
-    {
-        TimedLaunch tl(kFrameMean, st);
-        if (a.dtype == SHARPV_BF16)
-            hipLaunchKernelGGL(frame_mean_kernel<bf16_t>, dim3(a.n, slabs), dim3(1024), 0, st,
-                               (const bf16_t*)a.feats, a.f, a.d, ws.mean);
+    if (fused) {
+        // one workgroup per (slab, run of frames); about one workgroup per compute unit
+        int ranges = 256 / slabs;
+        ranges = ranges < 1 ? 1 : ranges;
+        ranges = ranges > a.n ? a.n : ranges;
+        const dim3 grid(slabs * ranges), block(kSlabThreads);
+        TimedLaunch tl(kFrameSlab, st);
+        if (a.f <= 144)
+            hipLaunchKernelGGL(frame_slab_kernel<9>, grid, block, 0, st, (const bf16_t*)a.feats, a.n, a.f, a.d, slabs,
+                               ranges, ws.aa, ws.am, ws.ab, ws.part_mm);
         else
-            hipLaunchKernelGGL(frame_mean_kernel<float>, dim3(a.n, slabs), dim3(1024), 0, st,
-                               (const float*)a.feats, a.f, a.d, ws.mean);
-    }
-    if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
-
-    {
+            hipLaunchKernelGGL(frame_slab_kernel<13>, grid, block, 0, st, (const bf16_t*)a.feats, a.n, a.f, a.d, slabs,
+                               ranges, ws.aa, ws.am, ws.ab, ws.part_mm);
+    } else {
+        {
+            TimedLaunch tl(kFrameMean, st);
+            if (a.dtype == SHARPV_BF16)
+                hipLaunchKernelGGL(frame_mean_kernel<bf16_t>, dim3(a.n, slabs), dim3(1024), 0, st,
+                                   (const bf16_t*)a.feats, a.f, a.d, ws.mean);
+            else
+                hipLaunchKernelGGL(frame_mean_kernel<float>, dim3(a.n, slabs), dim3(1024), 0, st,
+                                   (const float*)a.feats, a.f, a.d, ws.mean);
+        }
+        if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
         TimedLaunch tl(kTokenDots, st);
         if (a.dtype == SHARPV_BF16)
             hipLaunchKernelGGL(token_dots_kernel<bf16_t>, dim3((n_rows + 3) / 4), dim3(256), 0, st,
@@ -306,10 +510,11 @@ int launch_prune_tokens(const TokArgs& a) {
     {
         TimedLaunch tl(kFrameSelect, st);
         const int threads = (a.f + 63) / 64 * 64;
-        hipLaunchKernelGGL(frame_select_kernel, dim3(a.n), dim3(threads), 0, st, (const float*)ws.mean,
-                           (const float*)ws.aa, (const float*)ws.am, (const float*)ws.ab, a.frame_offsets, a.B,
-                           a.f, a.d, a.w, a.mode, a.K, a.min_keep, ws.local_idx, a.out_counts, a.out_scores,
-                           a.out_ratio);
+        hipLaunchKernelGGL(frame_select_kernel, dim3(a.n), dim3(threads), 0, st,
+                           fused ? (const float*)nullptr : (const float*)ws.mean, (const float*)ws.part_mm,
+                           (const float*)ws.aa, (const float*)ws.am, (const float*)ws.ab, ws.nparts, (size_t)n_rows,
+                           a.frame_offsets, a.B, a.f, a.d, a.w, a.mode, a.K, a.min_keep, ws.local_idx, a.out_counts,
+                           a.out_scores, a.out_ratio);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
 

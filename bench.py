@@ -146,10 +146,18 @@ def main() -> int:
     ms_stage2_layer = ms_stage2 / len(layers)
 
     # ------------------------------------------------------------------ per-kernel durations (events around every launch)
-    launches_per_step = 5 + 2 * len(layers)
-    sharpv.timing_enable(launches_per_step * args.steps + 8)
+    launches_per_step = 6 + 3 * len(layers)
+    n_ceiling = 6
+    sharpv.timing_enable(launches_per_step * args.steps + 2 * n_ceiling + 8)
     for _ in range(args.steps):
         step()
+    # practical HBM ceilings of this device: plain read and plain copy of buffers of the same size
+    # class (hidden states of different layers, so nothing is served from cache)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    for k in range(n_ceiling):
+        sharpv.stream_read(hidden[k % len(hidden)], sink)
+    for k in range(n_ceiling):
+        sharpv.stream_copy(tplan.out_feats, hidden[k % len(hidden)][:Nv])
     torch.cuda.synchronize()
     kern = {}
     for name in sharpv.KERNEL_NAMES:
@@ -171,8 +179,10 @@ def main() -> int:
 
     dom = "kv_cosine"
     dom_gbps = bytes_cos / (kern[dom]["avg_us"] * 1e-6) / 1e9
-    for name, b in (("kv_cosine", bytes_cos), ("kv_gather", bytes_gather_avg),
-                    ("frame_mean", Nv * row), ("token_dots", Nv * row), ("token_gather", 2 * kept_tokens * row)):
+    hid_bytes = hidden[0].numel() * esz
+    for name, b in (("kv_cosine", bytes_cos), ("kv_gather", bytes_gather_avg), ("frame_slab", Nv * row),
+                    ("frame_mean", Nv * row), ("token_dots", Nv * row), ("token_gather", 2 * kept_tokens * row),
+                    ("stream_read", hid_bytes), ("stream_copy", 2 * Nv * row)):
         if name in kern:
             kern[name]["alg_GBps"] = round(b / (kern[name]["avg_us"] * 1e-6) / 1e9, 1)
 
@@ -198,6 +208,8 @@ def main() -> int:
                      "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                      "alg_bytes_per_launch": int(bytes_cos), "avg_launch_us": kern[dom]["avg_us"]},
         "kernels": kern,
+        "hbm_ceiling": {"read_GBps": kern.get("stream_read", {}).get("alg_GBps"),
+                        "copy_GBps": kern.get("stream_copy", {}).get("alg_GBps")},
         "input_generation_s": round(gen_s, 1),
     }
 

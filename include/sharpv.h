@@ -144,11 +144,22 @@ int sharpv_prune_kv(
  * sharpv_timing_read synchronises on the recorded events and returns, for the kernel with the
  * given name, the number of timed launches and their summed duration in milliseconds.
  * Kernel names: "frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
- * "kv_cosine", "kv_mean", "kv_gather".  Not thread-safe; one device.
+ * "kv_cosine", "kv_mean", "kv_scan", "kv_gather", "stream_copy", "stream_read".  Not thread-safe; one device.
  */
 int sharpv_timing_enable(int max_launches);     /* creates the pool; resets earlier records */
 int sharpv_timing_disable(void);                /* destroys the pool */
 int sharpv_timing_read(const char* kernel_name, int* n_launches /* host */, double* total_ms /* host */);
+
+/* ------------------------------------------------------------------------------------------------
+ * Measurement aids (not part of the method): a plain streaming copy and a plain streaming read of
+ * `bytes` bytes (a multiple of 16; 16-byte aligned device pointers), enqueued on `stream`.  They give
+ * the practical HBM ceiling of the device next to the pruning kernels, and a copy of known size
+ * against which hardware byte counters can be scaled.  sharpv_stream_read writes one 4-byte word to
+ * `sink` (device) only if the data XORs to a magic value, i.e. practically never.
+ * Timed under the kernel names "stream_copy" and "stream_read".
+ */
+int sharpv_stream_copy(void* dst /* device */, const void* src /* device */, size_t bytes, void* stream);
+int sharpv_stream_read(const void* src /* device */, size_t bytes, uint32_t* sink /* device */, void* stream);
 
 #ifdef __cplusplus
 }

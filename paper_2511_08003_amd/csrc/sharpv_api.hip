@@ -19,7 +19,8 @@ struct TimingPool {
 } g_timing;
 
 const char* const kKernelNames[kNumKernels] = {"frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan",
-                                               "token_gather", "kv_cosine", "kv_mean", "kv_gather"};
+                                               "token_gather", "kv_cosine", "kv_mean", "kv_scan", "kv_gather",
+                                               "stream_copy", "stream_read"};
 }  // namespace
 
 void timing_begin(int kernel, hipStream_t st) {
@@ -48,6 +49,36 @@ static void timing_destroy() {
     t.used = 0;
     t.open = false;
     t.enabled = false;
+}
+
+// ---------------------------------------------------------------------------- measurement aids
+__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                          size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256 * 4;
+    for (size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x; i < n16; i += stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i + (size_t)k * 256 < n16) v[k] = src[i + (size_t)k * 256];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i + (size_t)k * 256 < n16) dst[i + (size_t)k * 256] = v[k];
+    }
+}
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * 256 * 4;
+    uint32_t acc = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x; i < n16; i += stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            v[k] = (i + (size_t)k * 256 < n16) ? src[i + (size_t)k * 256] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+    }
+    if (acc == 0x5ca1ab1eu) sink[0] = acc;
 }
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -196,6 +227,34 @@ int sharpv_prune_kv(const void* hidden, const void* orig, const void* K, const v
     a.out_cos = out_cos; a.out_mean_cos = out_mean_cos;
     a.workspace = workspace; a.stream = (hipStream_t)stream;
     return launch_prune_kv(a);
+}
+
+int sharpv_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (dst == nullptr || src == nullptr) return SHARPV_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return SHARPV_ERR_SHAPE;
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 1023) / 1024;
+    const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
+    {
+        TimedLaunch tl(kStreamCopy, (hipStream_t)stream);
+        hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                           (uint4*)dst, n16);
+    }
+    return hipGetLastError() == hipSuccess ? SHARPV_OK : SHARPV_ERR_DEVICE;
+}
+
+int sharpv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+    if (src == nullptr || sink == nullptr) return SHARPV_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || !aligned(src, 16) || !aligned(sink, 4)) return SHARPV_ERR_SHAPE;
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 1023) / 1024;
+    const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
+    {
+        TimedLaunch tl(kStreamRead, (hipStream_t)stream);
+        hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, n16,
+                           sink);
+    }
+    return hipGetLastError() == hipSuccess ? SHARPV_OK : SHARPV_ERR_DEVICE;
 }
 
 int sharpv_timing_enable(int max_launches) {

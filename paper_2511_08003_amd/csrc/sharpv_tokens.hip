@@ -19,7 +19,8 @@
 //                 (score descending, index ascending) against the scores staged in LDS, and the
 //                 frame's kept rows in ascending order.
 //   count_scan    exclusive scan of the per-frame kept counts.
-//   token_gather  copies the kept rows into the compacted stream and writes their indices.
+//   token_gather  copies the kept rows into the compacted stream and writes their indices, one
+//                 wavefront per kept row.
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
@@ -434,33 +435,47 @@ __global__ __launch_bounds__(1024) void count_scan_kernel(const int32_t* __restr
 }
 
 // ---------------------------------------------------------------------------- compaction
-constexpr int kGatherSplit = 16;    // workgroups (of four wavefronts) per frame
-__global__ __launch_bounds__(256) void token_gather_kernel(const char* __restrict__ feats, int f, int row_bytes,
-                                                           const int32_t* __restrict__ local_idx,
-                                                           const int32_t* __restrict__ counts,
+// One wavefront per kept row j of the compacted stream: its frame is found by bisection of the
+// offsets (staged in LDS when they fit), its source row from the frame's kept list;
+// out_feats[j] = feats[out_idx[j]].
+constexpr int kOffsetsInLds = 4096;
+__global__ __launch_bounds__(256) void token_gather_kernel(const char* __restrict__ feats, int row_bytes, int n, int f,
                                                            const int32_t* __restrict__ offsets,
+                                                           const int32_t* __restrict__ local_idx,
                                                            int32_t* __restrict__ out_idx, char* __restrict__ out_feats) {
-    const int t = blockIdx.x;
+    __shared__ int soff[kOffsetsInLds];
     const int lane = threadIdx.x & 63;
-    const int q = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int cnt = counts[t];
-    if (q >= cnt) return;
-    const int off = offsets[t];
+    const int total = offsets[n];
+    if ((int)blockIdx.x * 4 >= total) return;
+    const bool staged = n + 1 <= kOffsetsInLds;
+    if (staged) {
+        for (int i = threadIdx.x; i <= n; i += 256) soff[i] = offsets[i];
+        __syncthreads();
+    }
     const int units = row_bytes / 16;
-    for (int r = q; r < cnt; r += kGatherSplit * 4) {            // one wavefront per kept row
-        const int src_row = local_idx[(size_t)t * f + r];
+    for (int j = blockIdx.x * 4 + (threadIdx.x >> 6); j < total; j += gridDim.x * 4) {
+        int lo = 0, hi = n;                  // offsets[lo] <= j < offsets[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            const int v = staged ? soff[mid] : offsets[mid];
+            if (v <= j) lo = mid; else hi = mid;
+        }
+        const int first = staged ? soff[lo] : offsets[lo];
+        const int src_row = local_idx[(size_t)lo * f + (j - first)];
+        if (lane == 0) out_idx[j] = src_row;
         const uint4* src = reinterpret_cast<const uint4*>(feats + (size_t)src_row * row_bytes);
-        uint4* dst = reinterpret_cast<uint4*>(out_feats + (size_t)(off + r) * row_bytes);
+        uint4* dst = reinterpret_cast<uint4*>(out_feats + (size_t)j * row_bytes);
         for (int u0 = lane; u0 < units; u0 += 64 * 8) {          // eight 16-byte loads in flight per lane
             uint4 v[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (u0 + 64 * k < units) v[k] = src[u0 + 64 * k];
+            for (int k = 0; k < 8; ++k) {                        // loads carry no predicate (index clamped)
+                const int u = u0 + 64 * k;
+                v[k] = src[u < units ? u : units - 1];
+            }
 #pragma unroll
             for (int k = 0; k < 8; ++k)
                 if (u0 + 64 * k < units) dst[u0 + 64 * k] = v[k];
         }
-        if (lane == 0) out_idx[off + r] = src_row;
     }
 }
 
@@ -527,9 +542,10 @@ int launch_prune_tokens(const TokArgs& a) {
 
     {
         TimedLaunch tl(kTokenGather, st);
-        hipLaunchKernelGGL(token_gather_kernel, dim3(a.n, kGatherSplit), dim3(256), 0, st, (const char*)a.feats, a.f,
-                           (int)(a.d * esz), (const int32_t*)ws.local_idx, (const int32_t*)a.out_counts,
-                           (const int32_t*)a.out_offsets, a.out_idx, (char*)a.out_feats);
+        const int want = (n_rows + 3) / 4;
+        hipLaunchKernelGGL(token_gather_kernel, dim3(want < 2048 ? want : 2048), dim3(256), 0, st,
+                           (const char*)a.feats, (int)(a.d * esz), a.n, a.f, (const int32_t*)a.out_offsets,
+                           (const int32_t*)ws.local_idx, a.out_idx, (char*)a.out_feats);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
     return SHARPV_OK;

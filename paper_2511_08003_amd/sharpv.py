@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsharpv.so")
 F32, BF16 = 0, 1
 OK = 0
 KERNEL_NAMES = ("frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
-                "kv_cosine", "kv_mean", "kv_gather")
+                "kv_cosine", "kv_mean", "kv_scan", "kv_gather", "stream_copy", "stream_read")
 
 
 class Params(C.Structure):
@@ -58,6 +58,10 @@ def load() -> C.CDLL:
     L.sharpv_prune_kv.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, ip, ip, ip, C.c_int, C.c_int, C.c_int,
                                   C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64,
                                   fp, fp, vp, C.c_size_t, vp]
+    L.sharpv_stream_copy.restype = C.c_int
+    L.sharpv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    L.sharpv_stream_read.restype = C.c_int
+    L.sharpv_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
     L.sharpv_timing_enable.restype = C.c_int
     L.sharpv_timing_enable.argtypes = [C.c_int]
     L.sharpv_timing_disable.restype = C.c_int
@@ -226,6 +230,23 @@ def prune_kv(hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch
     plan = KvPlan(B, S, n_vis, d, H, D, params, device=hidden.device, mean_cos=mean_cos)
     check(plan.run(hidden, orig, K, V, vis_start0, seq_offsets, vis_start, vis_offsets, layer), "sharpv_prune_kv")
     return plan.results()
+
+
+# ----------------------------------------------------------------------------- measurement aids
+def stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain streaming copy of src's bytes into dst (both contiguous GPU tensors of equal byte size)."""
+    _require_gpu(dst, src)
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst is smaller than src")
+    check(load().sharpv_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream()), "sharpv_stream_copy")
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Plain streaming read of src's bytes; `sink` is a GPU int32 tensor with at least one element."""
+    _require_gpu(src, sink)
+    check(load().sharpv_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream()),
+          "sharpv_stream_read")
 
 
 # ----------------------------------------------------------------------------- event timing

@@ -74,14 +74,27 @@ constexpr int kSlabThreads = 512;   // 16 row groups x 32 lanes
 // byte offsets.
 template <int KR>
 __device__ __forceinline__ void load_slab(RawChunk<bf16_t> (&buf)[KR], const char* __restrict__ frame_base,
-                                          uint32_t lane_off, uint32_t row16_bytes, int f, int g, bool live) {
+                                          uint32_t chunk_off, uint32_t row_bytes, int f, int g) {
+    // Every lane loads from a valid address (row and chunk indices are clamped by the caller / here),
+    // so that no load sits under a predicate and all of them are in flight together; lanes and rows
+    // outside the frame are zeroed later by mask_slab.
 #pragma unroll
     for (int k = 0; k < KR; ++k) {
         const int i = g + 16 * k;
-        if (live && i < f)
-            buf[k].q = *reinterpret_cast<const uint4*>(frame_base + (lane_off + (uint32_t)k * row16_bytes));
-        else
-            buf[k] = zero_raw<bf16_t>();
+        const uint32_t ic = (uint32_t)(i < f ? i : f - 1);
+        buf[k].q = *reinterpret_cast<const uint4*>(frame_base + (ic * row_bytes + chunk_off));
+    }
+}
+
+template <int KR>
+__device__ __forceinline__ void mask_slab(RawChunk<bf16_t> (&buf)[KR], int f, int g, bool live) {
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+        const bool valid = live && (g + 16 * k < f);
+        buf[k].q.x = valid ? buf[k].q.x : 0u;
+        buf[k].q.y = valid ? buf[k].q.y : 0u;
+        buf[k].q.z = valid ? buf[k].q.z : 0u;
+        buf[k].q.w = valid ? buf[k].q.w : 0u;
     }
 }
 
@@ -124,19 +137,21 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
     float* const pm = part_am + (size_t)slab * N;
     float* const pb = part_ab + (size_t)slab * N;
     const size_t frame_bytes = (size_t)f * d * sizeof(bf16_t);
-    const uint32_t lane_off = (uint32_t)(((size_t)g * d + (size_t)c * kChunk) * sizeof(bf16_t));
-    const uint32_t row16_bytes = (uint32_t)(16u * (uint32_t)d * sizeof(bf16_t));
+    const int nchunks = d / kChunk;
+    const uint32_t chunk_off = (uint32_t)((live ? c : nchunks - 1) * kChunk * (int)sizeof(bf16_t));
+    const uint32_t row_bytes = (uint32_t)d * (uint32_t)sizeof(bf16_t);
     const char* const fbase = reinterpret_cast<const char*>(feats);
     const bool lead = (l & 15) == 0;             // lanes 0 and 16 of each half hold the two results of a pair
     const bool second = l != 0;
 
     RawChunk<bf16_t> cur[KR], nxt[KR];
     const int tb = t0 > 0 ? t0 - 1 : t0;
-    load_slab<KR>(cur, fbase + (size_t)tb * frame_bytes, lane_off, row16_bytes, f, g, live);
+    load_slab<KR>(cur, fbase + (size_t)tb * frame_bytes, chunk_off, row_bytes, f, g);
+    mask_slab<KR>(cur, f, g, live);
 
     for (int t = tb; t < t1; ++t) {
         const bool has_next = t + 1 < t1;
-        if (has_next) load_slab<KR>(nxt, fbase + (size_t)(t + 1) * frame_bytes, lane_off, row16_bytes, f, g, live);
+        if (has_next) load_slab<KR>(nxt, fbase + (size_t)(t + 1) * frame_bytes, chunk_off, row_bytes, f, g);
 
         if (t >= t0) {
             // column sums: rows of class g (even k) and class g+16 (odd k), each ascending; the
@@ -192,6 +207,7 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
         }
 
         if (has_next) {                          // share of x.x_prev of frame t+1, two rows per tree
+            mask_slab<KR>(nxt, f, g, live);      // first use of the next frame: its loads have to land here
             forget_unpacked<KR>(cur);
             const size_t row1 = (size_t)(t + 1) * f;
 #pragma unroll

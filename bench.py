@@ -186,6 +186,20 @@ def main() -> int:
         if name in kern:
             kern[name]["alg_GBps"] = round(b / (kern[name]["avg_us"] * 1e-6) / 1e9, 1)
 
+    # HBM bytes of the dominant kernel from the committed counter runs, valid only while the kernel
+    # sources are the ones those runs were taken on
+    traffic = None
+    try:
+        import hashlib
+        csrc = os.path.join(ROOT, "paper_2511_08003_amd", "csrc")
+        sha = hashlib.sha256(b"".join(open(os.path.join(csrc, fn), "rb").read()
+                                      for fn in sorted(os.listdir(csrc)))).hexdigest()
+        rec = json.load(open(os.path.join(ROOT, "profiles", "kv_cosine_c5_256f_traffic.json")))
+        if rec.get("sources_sha256") == sha and rec.get("workload") == cfg.name and len(layers) == cfg.n_layers:
+            traffic = rec["traffic_bytes_per_launch"]
+    except Exception:
+        traffic = None
+
     out = {
         "metric": "visual tokens/sec through score+select+compact; KV-prune GB/s vs HBM peak",
         "value": round(tokens_per_s, 1),
@@ -205,7 +219,7 @@ def main() -> int:
                      "GBps": round(gbps_stage2, 1), "frac_hbm_peak": round(gbps_stage2 / HBM_PEAK_GBPS, 4)},
         "tokens_per_s_whole_step": round(Nv / (ms_per_step * 1e-3), 1),
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "alg_bytes_per_launch": int(bytes_cos), "avg_launch_us": kern[dom]["avg_us"]},
         "kernels": kern,
         "hbm_ceiling": {"read_GBps": kern.get("stream_read", {}).get("alg_GBps"),

@@ -138,4 +138,22 @@ __device__ __forceinline__ float dissim_from_dots(float xy, float xx, float yy) 
     return __builtin_sqrtf(fmaxf(q, 0.0f));
 }
 
+// Inclusive integer prefix sum over a 1024-thread workgroup: shuffle scan inside each wavefront,
+// the 16 wavefront totals through LDS.  (Integers: any order gives the same sums.)
+__device__ __forceinline__ int block_inclusive_scan_1024(int v, int* wave_tot /* LDS [16] */) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        const int u = __shfl_up(v, s);
+        if (lane >= s) v += u;
+    }
+    if (lane == 63) wave_tot[wave] = v;
+    __syncthreads();
+    int before = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) before += w < wave ? wave_tot[w] : 0;
+    return v + before;
+}
+
 }  // namespace sharpv

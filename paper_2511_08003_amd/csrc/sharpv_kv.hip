@@ -204,28 +204,23 @@ __global__ __launch_bounds__(64) void kv_mask_from_mean_kernel(SeqDesc sd, int S
 // the kept positions per sequence.
 __global__ __launch_bounds__(1024) void kv_scan_kernel(const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S,
                                                        int32_t* __restrict__ word_base, int32_t* __restrict__ out_count) {
-    __shared__ int part[1024];
+    __shared__ int wave_tot[16];
+    __shared__ int s_total;
     const int tid = threadIdx.x;
     const int seg = (n_words + 1023) / 1024;
     const int lo = tid * seg;
     const int hi = lo + seg < n_words ? lo + seg : n_words;
     int s = 0;
     for (int j = lo; j < hi; ++j) s += __popc((unsigned)mask16[j]);
-    part[tid] = s;
-    __syncthreads();
-    for (int step = 1; step < 1024; step <<= 1) {
-        const int v = tid >= step ? part[tid - step] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    int run = part[tid] - s;
+    const int incl = block_inclusive_scan_1024(s, wave_tot);
+    int run = incl - s;
     for (int j = lo; j < hi; ++j) {
         word_base[j] = run;
         run += __popc((unsigned)mask16[j]);
     }
-    const int total = part[1023];
+    if (tid == 1023) s_total = incl;
     __syncthreads();                             // word_base is read below by other threads
+    const int total = s_total;
     // kept positions in [0, pos)
     auto kept_before = [&](int pos) -> int {
         const int w = pos / kMaskWord;

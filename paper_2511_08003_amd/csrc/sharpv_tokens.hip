@@ -349,20 +349,49 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
     float score = 0.0f;
     if (i < f) {
         const size_t r = (size_t)t * f + i;
-        // block shares added in ascending block order (a single share when the rows were summed whole)
+        // block shares added in ascending block order (a single share when the rows were summed whole);
+        // the loads of eight shares are issued together (index clamped, so none sits under a predicate)
         float xx = 0.0f, xm = 0.0f, xp = 0.0f, pp = 0.0f;
         if (nparts == 1) {
             xx = aa[r]; xm = am[r];
             if (!first) { xp = ab[r]; pp = aa[r - f]; }
-        } else {
-            for (int sb = 0; sb < nparts; ++sb) {
-                const size_t o = (size_t)sb * part_stride + r;
-                xx = xx + aa[o];
-                xm = xm + am[o];
-                if (!first) {
-                    xp = xp + ab[o];
-                    pp = pp + aa[o - f];
+        } else if (first) {
+            for (int s0 = 0; s0 < nparts; s0 += 8) {
+                float va[8], vm[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int sb = s0 + k < nparts ? s0 + k : nparts - 1;
+                    const size_t o = (size_t)sb * part_stride + r;
+                    va[k] = aa[o];
+                    vm[k] = am[o];
                 }
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (s0 + k < nparts) {
+                        xx = xx + va[k];
+                        xm = xm + vm[k];
+                    }
+            }
+        } else {
+            for (int s0 = 0; s0 < nparts; s0 += 8) {
+                float va[8], vm[8], vb[8], vp[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int sb = s0 + k < nparts ? s0 + k : nparts - 1;
+                    const size_t o = (size_t)sb * part_stride + r;
+                    va[k] = aa[o];
+                    vm[k] = am[o];
+                    vb[k] = ab[o];
+                    vp[k] = aa[o - f];
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (s0 + k < nparts) {
+                        xx = xx + va[k];
+                        xm = xm + vm[k];
+                        xp = xp + vb[k];
+                        pp = pp + vp[k];
+                    }
             }
         }
         const float S = dissim_from_dots(xm, xx, mm);                        // Eq.2
@@ -427,27 +456,20 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
 // ---------------------------------------------------------------------------- exclusive scan of the counts
 __global__ __launch_bounds__(1024) void count_scan_kernel(const int32_t* __restrict__ counts, int n,
                                                           int32_t* __restrict__ offsets) {
-    __shared__ int part[1024];
+    __shared__ int wave_tot[16];
     const int tid = threadIdx.x;
     const int seg = (n + 1023) / 1024;
     const int lo = tid * seg;
     const int hi = lo + seg < n ? lo + seg : n;
     int s = 0;
     for (int j = lo; j < hi; ++j) s += counts[j];
-    part[tid] = s;
-    __syncthreads();
-    for (int step = 1; step < 1024; step <<= 1) {
-        const int v = tid >= step ? part[tid - step] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    int run = part[tid] - s;                 // exclusive prefix of this thread's segment
+    const int incl = block_inclusive_scan_1024(s, wave_tot);
+    int run = incl - s;                      // exclusive prefix of this thread's segment
     for (int j = lo; j < hi; ++j) {
         offsets[j] = run;
         run += counts[j];
     }
-    if (tid == 1023) offsets[n] = part[1023];
+    if (tid == 1023) offsets[n] = incl;
 }
 
 // ---------------------------------------------------------------------------- compaction

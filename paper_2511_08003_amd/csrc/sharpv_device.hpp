@@ -52,6 +52,22 @@ template <> __device__ __forceinline__ RawChunk<float> zero_raw<float>() {
     return r;
 }
 
+// Streaming accesses: data that is touched once and should not displace anything in the caches.
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+    uint4 r;
+    r.x = __builtin_nontemporal_load(&p->x);
+    r.y = __builtin_nontemporal_load(&p->y);
+    r.z = __builtin_nontemporal_load(&p->z);
+    r.w = __builtin_nontemporal_load(&p->w);
+    return r;
+}
+__device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
+    __builtin_nontemporal_store(v.x, &p->x);
+    __builtin_nontemporal_store(v.y, &p->y);
+    __builtin_nontemporal_store(v.z, &p->z);
+    __builtin_nontemporal_store(v.w, &p->w);
+}
+
 // bf16 -> float32 is exact: the 16 bits become the high half of the float.
 __device__ __forceinline__ void unpack(const RawChunk<bf16_t>& r, float (&v)[8]) {
     v[0] = __uint_as_float(r.q.x << 16); v[1] = __uint_as_float(r.q.x & 0xffff0000u);

@@ -53,7 +53,6 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct KvWorkspace {
     unsigned long long* group_mask;  // [n_groups] keep mask of 64 positions (written as 4 x 16 bits)
-    int32_t* word_base;              // [ceil(S/16)] kept positions before each 16-bit mask word
     int32_t* drop_seq;               // [B]
     float* cosv;                     // [n_vis]
     size_t bytes;
@@ -65,7 +64,6 @@ inline KvWorkspace carve_kv_workspace(void* base, int B, int S, int n_vis) {
     size_t off = 0;
     KvWorkspace w;
     w.group_mask = (unsigned long long*)(p + off);  off += align_up(n_groups * 8);
-    w.word_base = (int32_t*)(p + off);              off += align_up(n_groups * 4 * 4);
     w.drop_seq = (int32_t*)(p + off);               off += align_up((size_t)B * 4);
     w.cosv = (float*)(p + off);                     off += align_up((size_t)n_vis * 4);
     w.bytes = off;
@@ -108,7 +106,7 @@ inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d, int dty
 
 // ---------------------------------------------------------------------------- event timing
 enum KernelId { kFrameSlab = 0, kFrameMean, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
-                kKvCosine, kKvMean, kKvScan, kKvGather, kStreamCopy, kStreamRead, kNumKernels };
+                kKvCosine, kKvMean, kKvGather, kStreamCopy, kStreamRead, kNumKernels };
 
 void timing_begin(int kernel, hipStream_t st);
 void timing_end(int kernel, hipStream_t st);

@@ -8,10 +8,9 @@
 //               decides Eq.7; the workgroup leaves one 16-bit word of the keep mask.
 //   kv_mean     one workgroup per sequence: mean cosine of its visual tokens in a fixed order
 //               (only launched when the mean is asked for or decides, kv_mode 1).
-//   kv_scan     one workgroup: exclusive prefix of the kept counts of the mask words, and the kept
-//               positions per sequence.
-//   kv_gather   one workgroup per mask word (16 positions): rank inside the word by popcount, then
-//               batched 16-byte copies of the kept K and V rows, plane by plane.
+//   kv_gather   one workgroup per mask word (16 positions): output offset = popcount of the preceding
+//               mask words, rank inside the word by popcount, then batched 16-byte copies of the kept
+//               K and V rows, plane by plane.  A last workgroup writes the per-sequence counts.
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
@@ -200,47 +199,36 @@ __global__ __launch_bounds__(64) void kv_mask_from_mean_kernel(SeqDesc sd, int S
     if (lane == 0) group_mask[group] = m;
 }
 
-// One workgroup: exclusive prefix of the kept counts of the 16-bit mask words (-> word_base), and
-// the kept positions per sequence.
-__global__ __launch_bounds__(1024) void kv_scan_kernel(const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S,
-                                                       int32_t* __restrict__ word_base, int32_t* __restrict__ out_count) {
-    __shared__ int wave_tot[16];
-    __shared__ int s_total;
-    const int tid = threadIdx.x;
-    const int seg = (n_words + 1023) / 1024;
-    const int lo = tid * seg;
-    const int hi = lo + seg < n_words ? lo + seg : n_words;
-    int s = 0;
-    for (int j = lo; j < hi; ++j) s += __popc((unsigned)mask16[j]);
-    const int incl = block_inclusive_scan_1024(s, wave_tot);
-    int run = incl - s;
-    for (int j = lo; j < hi; ++j) {
-        word_base[j] = run;
-        run += __popc((unsigned)mask16[j]);
-    }
-    if (tid == 1023) s_total = incl;
-    __syncthreads();                             // word_base is read below by other threads
-    const int total = s_total;
-    // kept positions in [0, pos)
-    auto kept_before = [&](int pos) -> int {
-        const int w = pos / kMaskWord;
-        if (w >= n_words) return total;
-        const int r = pos % kMaskWord;
-        return word_base[w] + (r ? __popc((unsigned)mask16[w] & ((1u << r) - 1u)) : 0);
-    };
-    if (sd.seq_offsets == nullptr) {
-        if (tid == 0) out_count[0] = total;
-    } else {
-        for (int b = tid; b < sd.B; b += 1024)
-            out_count[b] = kept_before(sd.seq_offsets[b + 1]) - kept_before(sd.seq_offsets[b]);
-    }
-}
-
 constexpr int kGatherThreads = 256;
+
+// Number of kept positions in [0, pos), pos <= S, summed by the whole workgroup from the 16-bit mask
+// words (every word below ceil(S/16) is complete: kv_cosine clears the bits of positions >= S).
+__device__ __forceinline__ int kept_before(const uint16_t* __restrict__ mask16, int pos, int* scratch) {
+    const int w16 = pos / kMaskWord;             // complete 16-bit words below pos
+    const int w64 = w16 / 4;
+    const unsigned long long* m64 = reinterpret_cast<const unsigned long long*>(mask16);
+    int part = 0;
+    for (int j = threadIdx.x; j < w64; j += kGatherThreads) part += __popcll(m64[j]);
+    if ((int)threadIdx.x < w16 - w64 * 4) part += __popc((unsigned)mask16[w64 * 4 + threadIdx.x]);
+    if (threadIdx.x == 0) {
+        const int r = pos % kMaskWord;
+        if (r) part += __popc((unsigned)mask16[w16] & ((1u << r) - 1u));
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) part += __shfl_xor(part, s);
+    __syncthreads();                             // scratch may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = part;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kGatherThreads / 64; ++w) tot += scratch[w];
+    return tot;
+}
 constexpr int kGatherBatch = 8;     // 16-byte loads in flight per lane
 
-// One workgroup per mask word (16 packed positions).  Kept row r of the word goes to output row
-// word_base + r of every K / V head plane; lanes walk (r, 16-byte piece) so that one wavefront reads
+// One workgroup per mask word (16 packed positions).  Its output offset is the number of kept positions
+// before the word (popcounts of the preceding mask words, summed by the workgroup).  Kept row r of the
+// word goes to output row offset + r of every K / V head plane; lanes walk (r, 16-byte piece) so that one wavefront reads
 // and writes whole consecutive rows of one plane, and the planes are taken in batches with all loads
 // of a batch issued before its stores.  CH = number of heads when known at compile time (the loads
 // of a batch then carry no predicate, which is what lets them overlap); CH = 0 takes any H and
@@ -249,12 +237,27 @@ template <int CH>
 __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
     char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H_any,
-    const uint16_t* __restrict__ mask16, const int32_t* __restrict__ word_base, int32_t* __restrict__ out_idx) {
+    const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S, int32_t* __restrict__ out_idx,
+    int32_t* __restrict__ out_count) {
+    __shared__ int scratch[kGatherThreads / 64];
     const int H = CH > 0 ? CH : H_any;
     const int word = blockIdx.x;
+    if (word == n_words) {                       // extra workgroup: kept positions per sequence
+        if (sd.seq_offsets == nullptr) {
+            const int tot = kept_before(mask16, S, scratch);
+            if (threadIdx.x == 0) out_count[0] = tot;
+        } else {
+            for (int b = 0; b < sd.B; ++b) {
+                const int lo = kept_before(mask16, sd.seq_offsets[b], scratch);
+                const int hi = kept_before(mask16, sd.seq_offsets[b + 1], scratch);
+                if (threadIdx.x == 0) out_count[b] = hi - lo;
+            }
+        }
+        return;
+    }
     const unsigned mask = mask16[word];
     if (mask == 0u) return;                      // nothing kept here (uniform over the workgroup)
-    const int base = word_base[word];
+    const int base = kept_before(mask16, word * kMaskWord, scratch);
     const int cnt = __popc(mask);
     const int pieces = row_bytes / 16;
     const int units = cnt * pieces;              // 16-byte units of one plane of this word
@@ -277,14 +280,14 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
                 int p = p0 + k;
                 if (CH == 0) p = p < planes ? p : planes - 1;          // a valid plane, loaded twice
                 const int h = p < H ? p : p - H;
-                t[k] = *reinterpret_cast<const uint4*>((p < H ? K : V) + h * stride_h_bytes + src_off);
+                t[k] = load_stream(reinterpret_cast<const uint4*>((p < H ? K : V) + h * stride_h_bytes + src_off));
             }
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {
                 const int p = p0 + k;
                 if (CH > 0 || p < planes) {
                     const int h = p < H ? p : p - H;
-                    *reinterpret_cast<uint4*>((p < H ? K_out : V_out) + h * out_stride_h_bytes + dst_off) = t[k];
+                    store_stream(reinterpret_cast<uint4*>((p < H ? K_out : V_out) + h * out_stride_h_bytes + dst_off), t[k]);
                 }
             }
         }
@@ -325,19 +328,13 @@ int launch_prune_kv(const KvArgs& a) {
     const int n_words = (a.S + kMaskWord - 1) / kMaskWord;
     const uint16_t* mask16 = reinterpret_cast<const uint16_t*>(ws.group_mask);
     {
-        TimedLaunch tl(kKvScan, st);
-        hipLaunchKernelGGL(kv_scan_kernel, dim3(1), dim3(1024), 0, st, mask16, n_words, a.sd, a.S, ws.word_base,
-                           a.out_count);
-    }
-    if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
-    {
         TimedLaunch tl(kKvGather, st);
 #define SHARPV_GATHER(CH_)                                                                                          \
-    hipLaunchKernelGGL((kv_gather_kernel<CH_>), dim3(n_words), dim3(kGatherThreads), 0, st, (const char*)a.K,       \
+    hipLaunchKernelGGL((kv_gather_kernel<CH_>), dim3(n_words + 1), dim3(kGatherThreads), 0, st, (const char*)a.K,   \
                        (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),                                  \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
-                       (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16,                    \
-                       (const int32_t*)ws.word_base, a.out_idx)
+                       (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
+                       a.S, a.out_idx, a.out_count)
         switch (a.H) {
             case 1: SHARPV_GATHER(1); break;
             case 2: SHARPV_GATHER(2); break;

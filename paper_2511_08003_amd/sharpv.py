@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsharpv.so")
 F32, BF16 = 0, 1
 OK = 0
 KERNEL_NAMES = ("frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
-                "kv_cosine", "kv_mean", "kv_scan", "kv_gather", "stream_copy", "stream_read")
+                "kv_cosine", "kv_mean", "kv_gather", "stream_copy", "stream_read")
 
 
 class Params(C.Structure):

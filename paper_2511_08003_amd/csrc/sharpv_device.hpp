@@ -20,6 +20,22 @@ constexpr int kBlockElems = kChunk * kBlockChunks;   // 256
 
 struct bf16_t { uint16_t bits; };
 
+// Streaming accesses: data that is touched once and should not displace anything in the caches.
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+    uint4 r;
+    r.x = __builtin_nontemporal_load(&p->x);
+    r.y = __builtin_nontemporal_load(&p->y);
+    r.z = __builtin_nontemporal_load(&p->z);
+    r.w = __builtin_nontemporal_load(&p->w);
+    return r;
+}
+__device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
+    __builtin_nontemporal_store(v.x, &p->x);
+    __builtin_nontemporal_store(v.y, &p->y);
+    __builtin_nontemporal_store(v.z, &p->z);
+    __builtin_nontemporal_store(v.w, &p->w);
+}
+
 // ---------------------------------------------------------------------------- raw chunk loads
 template <typename T> struct RawChunk;
 template <> struct RawChunk<bf16_t> { uint4 q; };
@@ -39,6 +55,22 @@ template <> __device__ __forceinline__ RawChunk<float> load_raw<float>(const flo
     return r;
 }
 
+// The same loads marked as streaming (non-temporal).
+template <typename T> __device__ __forceinline__ RawChunk<T> load_raw_stream(const T* p);
+template <> __device__ __forceinline__ RawChunk<bf16_t> load_raw_stream<bf16_t>(const bf16_t* p) {
+    RawChunk<bf16_t> r;
+    r.q = load_stream(reinterpret_cast<const uint4*>(p));
+    return r;
+}
+template <> __device__ __forceinline__ RawChunk<float> load_raw_stream<float>(const float* p) {
+    RawChunk<float> r;
+    const uint4 a = load_stream(reinterpret_cast<const uint4*>(p));
+    const uint4 b = load_stream(reinterpret_cast<const uint4*>(p) + 1);
+    r.a = make_float4(__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(a.z), __uint_as_float(a.w));
+    r.b = make_float4(__uint_as_float(b.x), __uint_as_float(b.y), __uint_as_float(b.z), __uint_as_float(b.w));
+    return r;
+}
+
 template <typename T> __device__ __forceinline__ RawChunk<T> zero_raw();
 template <> __device__ __forceinline__ RawChunk<bf16_t> zero_raw<bf16_t>() {
     RawChunk<bf16_t> r;
@@ -50,22 +82,6 @@ template <> __device__ __forceinline__ RawChunk<float> zero_raw<float>() {
     r.a = make_float4(0.f, 0.f, 0.f, 0.f);
     r.b = r.a;
     return r;
-}
-
-// Streaming accesses: data that is touched once and should not displace anything in the caches.
-__device__ __forceinline__ uint4 load_stream(const uint4* p) {
-    uint4 r;
-    r.x = __builtin_nontemporal_load(&p->x);
-    r.y = __builtin_nontemporal_load(&p->y);
-    r.z = __builtin_nontemporal_load(&p->z);
-    r.w = __builtin_nontemporal_load(&p->w);
-    return r;
-}
-__device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
-    __builtin_nontemporal_store(v.x, &p->x);
-    __builtin_nontemporal_store(v.y, &p->y);
-    __builtin_nontemporal_store(v.z, &p->z);
-    __builtin_nontemporal_store(v.w, &p->w);
 }
 
 // bf16 -> float32 is exact: the 16 bits become the high half of the float.

@@ -43,8 +43,8 @@ __device__ __forceinline__ float row_cosine(const T* __restrict__ hrow, const T*
     for (int q = 0; q < NS; ++q) {
         const int c = q * 64 + lane;
         if (FULL || c < nchunks) {
-            rh[q] = load_raw<T>(hrow + (size_t)c * kChunk);
-            ro[q] = load_raw<T>(orow + (size_t)c * kChunk);
+            rh[q] = load_raw_stream<T>(hrow + (size_t)c * kChunk);
+            ro[q] = load_raw_stream<T>(orow + (size_t)c * kChunk);
         } else {
             rh[q] = zero_raw<T>();
             ro[q] = zero_raw<T>();

@@ -59,10 +59,10 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restric
         uint4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (i + (size_t)k * 256 < n16) v[k] = src[i + (size_t)k * 256];
+            v[k] = load_stream(src + (i + (size_t)k * 256 < n16 ? i + (size_t)k * 256 : n16 - 1));
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (i + (size_t)k * 256 < n16) dst[i + (size_t)k * 256] = v[k];
+            if (i + (size_t)k * 256 < n16) store_stream(dst + i + (size_t)k * 256, v[k]);
     }
 }
 
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
         uint4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            v[k] = (i + (size_t)k * 256 < n16) ? src[i + (size_t)k * 256] : make_uint4(0u, 0u, 0u, 0u);
+            v[k] = load_stream(src + (i + (size_t)k * 256 < n16 ? i + (size_t)k * 256 : i));
 #pragma unroll
         for (int k = 0; k < 4; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
     }

@@ -82,7 +82,7 @@ __device__ __forceinline__ void load_slab(RawChunk<bf16_t> (&buf)[KR], const cha
     for (int k = 0; k < KR; ++k) {
         const int i = g + 16 * k;
         const uint32_t ic = (uint32_t)(i < f ? i : f - 1);
-        buf[k].q = *reinterpret_cast<const uint4*>(frame_base + (ic * row_bytes + chunk_off));
+        buf[k].q = load_stream(reinterpret_cast<const uint4*>(frame_base + (ic * row_bytes + chunk_off)));
     }
 }
 
@@ -508,11 +508,11 @@ __global__ __launch_bounds__(256) void token_gather_kernel(const char* __restric
 #pragma unroll
             for (int k = 0; k < 8; ++k) {                        // loads carry no predicate (index clamped)
                 const int u = u0 + 64 * k;
-                v[k] = src[u < units ? u : units - 1];
+                v[k] = load_stream(src + (u < units ? u : units - 1));
             }
 #pragma unroll
             for (int k = 0; k < 8; ++k)
-                if (u0 + 64 * k < units) dst[u0 + 64 * k] = v[k];
+                if (u0 + 64 * k < units) store_stream(dst + u0 + 64 * k, v[k]);
         }
     }
 }

@@ -231,19 +231,26 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from oracle import canon
         canon.lib()
+        reps = 5
+        canon.prune_tokens(tok.feats, cfg.dtype, tok.frame_offsets)              # page the inputs in
         t0 = time.perf_counter()
-        canon.prune_tokens(tok.feats, cfg.dtype, tok.frame_offsets)
-        cpu_s1 = time.perf_counter() - t0
+        for _ in range(reps):
+            canon.prune_tokens(tok.feats, cfg.dtype, tok.frame_offsets)
+        cpu_s1 = (time.perf_counter() - t0) / reps
         l0, kv0 = host_layer0
         t0 = time.perf_counter()
-        ck = canon.prune_kv(kv0["hidden"], tok.feats.reshape(-1, d), kv0["K"], kv0["V"], cfg.dtype,
-                            lay.seq_offsets, lay.vis_start, lay.vis_offsets, M=0.2)
-        cpu_s2 = time.perf_counter() - t0
+        for _ in range(reps):
+            ck = canon.prune_kv(kv0["hidden"], tok.feats.reshape(-1, d), kv0["K"], kv0["V"], cfg.dtype,
+                                lay.seq_offsets, lay.vis_start, lay.vis_offsets, M=0.2)
+        cpu_s2 = (time.perf_counter() - t0) / reps
         b2 = bytes_cos + 4 * len(ck["idx"]) * kv_row + 4 * len(ck["idx"])
+        cores = canon.threads()
         out["cpu_baseline"] = {
-            "value": round(Nv / cpu_s1, 1), "unit": "visual tokens/s", "cores": canon.threads(), "kind": "oracle",
-            "sample": f"float32 canonical-order oracle (C, OpenMP): pre-LLM stage on all {n} frames of the workload "
-                      f"({cpu_s1:.2f} s); intra-LLM stage on layer {l0} ({cpu_s2:.2f} s)",
+            "value": round(Nv / cpu_s1, 1), "unit": "visual tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"float32 canonical-order oracle (C, OpenMP over frames / tokens, {cores} threads), mean of {reps} "
+                      f"runs: pre-LLM stage on all {n} frames of the workload ({cpu_s1:.3f} s per run); intra-LLM "
+                      f"stage on layer {l0} of the same workload ({cpu_s2:.3f} s per run); about "
+                      f"{reps * (cpu_s1 + cpu_s2) * cores:.0f} core-seconds in all",
             "kv_prune_GBps": round(b2 / cpu_s2 / 1e9, 3),
         }
     print(json.dumps(out), flush=True)

@@ -104,7 +104,8 @@ __device__ __forceinline__ float chain8(const float (&x)[8], const float (&y)[8]
     return c;
 }
 
-// Lane l of a 16-lane row receives the value of lane (l + n) mod 16 of the same row (DPP row rotate).
+// Lane l of a 16-lane row receives the value of lane (l - n) mod 16 of the same row (DPP row_ror:
+// values move towards higher lane numbers).
 template <int N> __device__ __forceinline__ float row_rotate(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
 }
@@ -138,6 +139,28 @@ __device__ __forceinline__ float tree32(float v) {
 __device__ __forceinline__ float tree32_pair(float a, float b) {
     const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
     return tree16_rows(__uint_as_float(r[0]) + __uint_as_float(r[1]));
+}
+
+// Four trees at a time.  The stride-16 step runs as in tree32_pair for (a, b) and for (c, d); at
+// stride 8 lanes 0-7 of every 16-lane row go on with the first pair and lanes 8-15 with the second
+// (each takes its own value and receives its stride-8 partner's by a rotation of the other
+// selection), and strides 4, 2, 1 are shared.  A rotation by s < 8 hands lane l the value of lane
+// l - s, so inside a group of 8 only lanes >= 4, then >= 6, then lane 7 keep receiving partners of
+// their own tree: lanes 7 / 15 / 23 / 31 of a half-wavefront end with TREE32 of a / c / b / d (the
+// same additions as the halving tree, operands swapped), the other lanes with mixtures.
+__device__ __forceinline__ float tree32_quad(float a, float b, float c, float d) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    const auto s = __builtin_amdgcn_permlane16_swap(__float_as_uint(c), __float_as_uint(d), false, false);
+    const float x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const float y = __uint_as_float(s[0]) + __uint_as_float(s[1]);
+    const bool upper = (threadIdx.x & 8) != 0;
+    const float own = upper ? y : x;
+    const float other = upper ? x : y;
+    float v = own + row_rotate<8>(other);
+    v = v + row_rotate<4>(v);
+    v = v + row_rotate<2>(v);
+    v = v + row_rotate<1>(v);
+    return v;
 }
 
 __device__ __forceinline__ float lane_value(float v, int lane) {

@@ -68,51 +68,23 @@ __global__ __launch_bounds__(1024) void frame_mean_kernel(const T* __restrict__ 
 // ---------------------------------------------------------------------------- fused mean + inner products
 constexpr int kSlabThreads = 512;   // 16 row groups x 32 lanes
 
-// Thread (g, l): lane l owns chunk l of the slab, row group g owns rows g, g+16, g+32, ... of a frame.
-// Row i belongs to class i % 32 of the column sum, i.e. class g for even k and class g+16 for odd k
-// (i = g + 16k).  KR = rows per thread, f <= 16*KR.  Loads use one uniform frame base plus 32-bit
-// byte offsets.
-template <int KR>
-__device__ __forceinline__ void load_slab(RawChunk<bf16_t> (&buf)[KR], const char* __restrict__ frame_base,
-                                          uint32_t chunk_off, uint32_t row_bytes, int f, int g) {
-    // Every lane loads from a valid address (row and chunk indices are clamped by the caller / here),
-    // so that no load sits under a predicate and all of them are in flight together; lanes and rows
-    // outside the frame are zeroed later by mask_slab.
-#pragma unroll
-    for (int k = 0; k < KR; ++k) {
-        const int i = g + 16 * k;
-        const uint32_t ic = (uint32_t)(i < f ? i : f - 1);
-        buf[k].q = load_stream(reinterpret_cast<const uint4*>(frame_base + (ic * row_bytes + chunk_off)));
-    }
-}
-
-template <int KR>
-__device__ __forceinline__ void mask_slab(RawChunk<bf16_t> (&buf)[KR], int f, int g, bool live) {
-#pragma unroll
-    for (int k = 0; k < KR; ++k) {
-        const bool valid = live && (g + 16 * k < f);
-        buf[k].q.x = valid ? buf[k].q.x : 0u;
-        buf[k].q.y = valid ? buf[k].q.y : 0u;
-        buf[k].q.z = valid ? buf[k].q.z : 0u;
-        buf[k].q.w = valid ? buf[k].q.w : 0u;
-    }
-}
-
-// Makes the compiler forget what it knows about the packed registers, so that widened copies of a
-// whole frame slab (eight floats per chunk) are recomputed where needed instead of being kept live.
-template <int KR>
-__device__ __forceinline__ void forget_unpacked(RawChunk<bf16_t> (&buf)[KR]) {
-#pragma unroll
-    for (int k = 0; k < KR; ++k)
-        asm volatile("" : "+v"(buf[k].q.x), "+v"(buf[k].q.y), "+v"(buf[k].q.z), "+v"(buf[k].q.w));
-}
-
 // A workgroup owns slab `slab` (256 columns = one block of the summation order) of the frames
-// [t0, t1).  Two frame slabs live in registers: the current frame and the next one, whose loads are
-// in flight while the current frame is worked on.  For the current frame: column sums -> frame-mean
-// slab -> the slab's share of x.x and x.mean per row.  Then, with the next frame landed, its share of
-// x.x_prev (next frame's rows against the current ones).  The run starts one frame early (t0-1) for
-// that last product only.
+// [t0, t1) and walks them in order.  Thread (g, l): lane l owns chunk l of the slab, row group g owns
+// rows g, g+16, g+32, ... of a frame (KR = ceil(f/16) rows per thread, so only the last of them can
+// fall outside the frame).  Row i belongs to class i % 32 of the column sum, i.e. class g for even k
+// and class g+16 for odd k (i = g + 16k).
+//
+// Two frame slabs live in registers as packed bf16: the frame that has just arrived (`curr`, frame
+// t) and the one before it (`prev`).  One pass over the thread's rows widens each of them once and
+// takes everything that needs them: the column sums of frame t, the slab's shares of x.x and
+// x.x_prev of frame t, and the share of x.mean of frame t-1, whose mean slab was finished at the end
+// of the previous step.  As soon as a row of `prev` has been widened its registers receive the same
+// row of frame t+1, so those loads are in flight for a whole step.  The two buffers swap roles from
+// step to step; x.mean of the run's last frame is taken after the loop.
+//
+// Every lane loads from a valid address (row and chunk indices are clamped) so that no load sits
+// under a per-lane predicate; lanes past the end of a row contribute zeros to the trees, and the
+// one row per thread that may lie past the frame is zeroed before it enters the column sums.
 template <int KR>
 __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* __restrict__ feats, int n, int f, int d,
                                                                   int nslabs, int ranges,
@@ -120,8 +92,10 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
                                                                   float* __restrict__ part_am,
                                                                   float* __restrict__ part_ab,
                                                                   float* __restrict__ part_mm) { // [n][nslabs]
-    __shared__ float sm[16][kBlockElems];        // column sums of classes g and g+16 already added
-    __shared__ float smean[kBlockElems];
+    // column c sits at index c + c/8 (one pad word per chunk of 8), which spreads a lane's 8
+    // consecutive words and the other lanes' over distinct LDS banks
+    __shared__ float sm[16][kBlockElems + kBlockChunks];   // column sums of classes g and g+16 already added
+    __shared__ float smean[kBlockElems + kBlockChunks];
     const int tid = threadIdx.x;
     const int l = tid & 31;
     const int g = tid >> 5;
@@ -130,109 +104,174 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
     const int t0 = (int)((long long)range * n / ranges);
     const int t1 = (int)((long long)(range + 1) * n / ranges);
     if (t0 >= t1) return;
-    const int c = slab * kBlockChunks + l;
-    const bool live = c < d / kChunk;
-    const size_t N = (size_t)n * f;
-    float* const pa = part_aa + (size_t)slab * N;
-    float* const pm = part_am + (size_t)slab * N;
-    float* const pb = part_ab + (size_t)slab * N;
-    const size_t frame_bytes = (size_t)f * d * sizeof(bf16_t);
     const int nchunks = d / kChunk;
+    const int c = slab * kBlockChunks + l;
+    const bool live = c < nchunks;
+    const size_t N = (size_t)n * f;
+    const size_t frame_bytes = (size_t)f * d * sizeof(bf16_t);
+    const char* const fbase = reinterpret_cast<const char*>(feats);
     const uint32_t chunk_off = (uint32_t)((live ? c : nchunks - 1) * kChunk * (int)sizeof(bf16_t));
     const uint32_t row_bytes = (uint32_t)d * (uint32_t)sizeof(bf16_t);
-    const char* const fbase = reinterpret_cast<const char*>(feats);
-    const bool lead = (l & 15) == 0;             // lanes 0 and 16 of each half hold the two results of a pair
-    const bool second = l != 0;
+    uint32_t off[KR];                            // byte offsets of the thread's chunks inside a frame
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+        const int i = g + 16 * k;
+        off[k] = (uint32_t)(i < f ? i : f - 1) * row_bytes + chunk_off;
+    }
+    const bool last_row_valid = g + 16 * (KR - 1) < f;
 
-    RawChunk<bf16_t> cur[KR], nxt[KR];
-    const int tb = t0 > 0 ? t0 - 1 : t0;
-    load_slab<KR>(cur, fbase + (size_t)tb * frame_bytes, chunk_off, row_bytes, f, g);
-    mask_slab<KR>(cur, f, g, live);
+    // tree32_quad(a, b, c, d) leaves a, c, b, d in lanes 7, 15, 23, 31 of a half-wavefront; this
+    // lane's quarter decides which result it stores and where.
+    const int quarter = l >> 3;
+    const bool qlead = (l & 7) == 7;
+    // (x.x, x.x_prev) of rows k and k+1 -> quarters 0..3 hold aa[k], aa[k+1], ab[k], ab[k+1]
+    const int pair_row = quarter & 1;
+    const bool pair_is_ab = (quarter & 2) != 0;
+    float* const pair_ptr = (pair_is_ab ? part_ab : part_aa) + (size_t)slab * N + g + 16 * pair_row;
+    // x.mean of rows k .. k+3 -> quarters 0..3 hold am[k], am[k+2], am[k+1], am[k+3]
+    const int mean_row = (quarter & 1) * 2 + (quarter >> 1);
+    float* const mean_ptr = part_am + (size_t)slab * N + g + 16 * mean_row;
 
-    for (int t = tb; t < t1; ++t) {
+    // Trees and stores of the x.mean shares of frame tm (four rows per tree, zero padding at the end).
+    auto mean_products = [&](const float (&am)[KR], const int tm, const bool store) {
+        float* const pm = mean_ptr + (size_t)tm * f;
+#pragma unroll
+        for (int k = 0; k < KR; k += 4) {
+            const float z = tree32_quad(am[k], k + 1 < KR ? am[k + 1] : 0.0f, k + 2 < KR ? am[k + 2] : 0.0f,
+                                        k + 3 < KR ? am[k + 3] : 0.0f);
+            const int r = k + mean_row;          // this lane's row slot
+            const bool ok = (k + 3 < KR - 1) || (r < KR - 1) || (r == KR - 1 && last_row_valid);
+            if (store && qlead && ok) pm[16 * k] = z;
+        }
+    };
+
+    RawChunk<bf16_t> A[KR], B[KR];
+    float m[8];                                  // this lane's chunk of the latest frame-mean slab
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m[j] = 0.0f;
+
+    auto step = [&](RawChunk<bf16_t> (&prev)[KR], RawChunk<bf16_t> (&curr)[KR], const int t) {
         const bool has_next = t + 1 < t1;
-        if (has_next) load_slab<KR>(nxt, fbase + (size_t)(t + 1) * frame_bytes, chunk_off, row_bytes, f, g);
-
-        if (t >= t0) {
-            // column sums: rows of class g (even k) and class g+16 (odd k), each ascending; the
-            // stride-16 level of the class tree adds the two right here
-            float pe[8], po[8];
+        const bool store_ab = t > 0;
+        const char* const nb = fbase + (size_t)(t + 1) * frame_bytes;
+        float* const pp = pair_ptr + (size_t)t * f;
+        // column sums: rows of class g (even k) and class g+16 (odd k), each ascending; the
+        // stride-16 level of the class tree adds the two right here
+        float pe[8], po[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) { pe[j] = 0.0f; po[j] = 0.0f; }
+        for (int j = 0; j < 8; ++j) { pe[j] = 0.0f; po[j] = 0.0f; }
+        float am[KR];
+        float aa_even = 0.0f, ab_even = 0.0f;
+        // keep "uniform frame base + 32-bit lane offset" addressing: without this the lane offsets are
+        // widened and added to the feature pointer once, outside the loop, at two registers per row
 #pragma unroll
-            for (int k = 0; k < KR; ++k) {
-                float v[8];
-                unpack(cur[k], v);
-                if (k & 1) {
+        for (int k = 0; k < KR; ++k) asm volatile("" : "+v"(off[k]));
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) po[j] = po[j] + v[j];
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) pe[j] = pe[j] + v[j];
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        for (int k = 0; k < KR; ++k) {
+            if (k == KR - 1) {                   // the only row that can lie past the frame
+                curr[k].q.x = last_row_valid ? curr[k].q.x : 0u;
+                curr[k].q.y = last_row_valid ? curr[k].q.y : 0u;
+                curr[k].q.z = last_row_valid ? curr[k].q.z : 0u;
+                curr[k].q.w = last_row_valid ? curr[k].q.w : 0u;
             }
+            float a[8], b[8];
+            unpack(curr[k], a);
+            unpack(prev[k], b);
+            if (k & 1) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) sm[g][l * 8 + j] = pe[j] + po[j];
-            forget_unpacked<KR>(cur);
-            __syncthreads();
-            if (tid < kBlockElems) {             // one thread per column: strides 8, 4, 2, 1 over the 16 sums
-                float q[16];
+                for (int j = 0; j < 8; ++j) po[j] = po[j] + a[j];
+            } else {
 #pragma unroll
-                for (int gg = 0; gg < 16; ++gg) q[gg] = sm[gg][tid];
-#pragma unroll
-                for (int st = 8; st >= 1; st >>= 1)
-#pragma unroll
-                    for (int ll = 0; ll < st; ++ll) q[ll] = q[ll] + q[ll + st];
-                smean[tid] = q[0] / (float)f;
+                for (int j = 0; j < 8; ++j) pe[j] = pe[j] + a[j];
             }
-            __syncthreads();
-            float m[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) m[j] = smean[l * 8 + j];
-            if (tid < 64) {                      // this slab's share of mean.mean
-                const float v = tree32(chain8(m, m));
-                if (tid == 0) part_mm[(size_t)t * nslabs + slab] = v;
+            float vaa = chain8(a, a), vab = chain8(a, b), vam = chain8(b, m);
+            if (has_next) prev[k].q = load_stream(reinterpret_cast<const uint4*>(nb + off[k]));
+            vaa = live ? vaa : 0.0f;
+            vab = live ? vab : 0.0f;
+            am[k] = live ? vam : 0.0f;
+            if (k & 1) {
+                const float z = tree32_quad(aa_even, ab_even, vaa, vab);
+                const bool ok = (k < KR - 1) || pair_row == 0 || last_row_valid;
+                if (qlead && ok && (store_ab || !pair_is_ab)) pp[16 * (k - 1)] = z;
+            } else if (k == KR - 1) {            // odd row count: the last row alone (quarters 0 and 2 store)
+                const float z = tree32_pair(vaa, vab);
+                if (qlead && pair_row == 0 && last_row_valid && (store_ab || !pair_is_ab)) pp[16 * k] = z;
+            } else {
+                aa_even = vaa;
+                ab_even = vab;
             }
-            const size_t row0 = (size_t)t * f;
-#pragma unroll
-            for (int k = 0; k < KR; ++k) {       // the slab's share of x.x (lanes 0-15) and x.mean (lanes 16-31)
-                const int i = g + 16 * k;
-                float a[8];
-                unpack(cur[k], a);
-                const float x = tree32_pair(chain8(a, a), chain8(a, m));
-                if (lead && i < f) (second ? pm : pa)[row0 + i] = x;
-                __builtin_amdgcn_sched_barrier(0);   // keep the rows' temporaries from piling up in registers
-            }
+            // Pin the row's results here: everything that needs the widened rows is finished before
+            // the next rows start, so their sixteen floats do not stay alive (the compiler otherwise
+            // sinks the column sums and the x.mean chains to the end of the step).
+            if (k & 1)
+                asm volatile("" : "+v"(po[0]), "+v"(po[1]), "+v"(po[2]), "+v"(po[3]), "+v"(po[4]), "+v"(po[5]),
+                                  "+v"(po[6]), "+v"(po[7]), "+v"(am[k]));
+            else
+                asm volatile("" : "+v"(pe[0]), "+v"(pe[1]), "+v"(pe[2]), "+v"(pe[3]), "+v"(pe[4]), "+v"(pe[5]),
+                                  "+v"(pe[6]), "+v"(pe[7]), "+v"(am[k]));
+            __builtin_amdgcn_sched_barrier(0);
         }
+        mean_products(am, t - 1, t > t0);
+        // The next step widens `curr` again (as its `prev`); make the compiler forget the widened
+        // copies instead of keeping eight floats per chunk alive across the step boundary.
+#pragma unroll
+        for (int k = 0; k < KR; ++k)
+            asm volatile("" : "+v"(curr[k].q.x), "+v"(curr[k].q.y), "+v"(curr[k].q.z), "+v"(curr[k].q.w));
 
-        if (has_next) {                          // share of x.x_prev of frame t+1, two rows per tree
-            mask_slab<KR>(nxt, f, g, live);      // first use of the next frame: its loads have to land here
-            forget_unpacked<KR>(cur);
-            const size_t row1 = (size_t)(t + 1) * f;
 #pragma unroll
-            for (int k = 0; k < KR; k += 2) {
-                const int i0 = g + 16 * k;
-                float a[8], b[8];
-                unpack(nxt[k], a);
-                unpack(cur[k], b);
-                const float ab0 = chain8(a, b);
-                if (k + 1 < KR) {
-                    float a1[8], b1[8];
-                    unpack(nxt[k + 1], a1);
-                    unpack(cur[k + 1], b1);
-                    const float z = tree32_pair(ab0, chain8(a1, b1));
-                    const int iz = second ? i0 + 16 : i0;
-                    if (lead && iz < f) pb[row1 + iz] = z;
-                } else {
-                    const float z = tree32(ab0);
-                    if (l == 0 && i0 < f) pb[row1 + i0] = z;
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int j = 0; j < 8; ++j) sm[g][l * 9 + j] = pe[j] + po[j];
+        __syncthreads();
+        if (tid < kBlockElems) {                 // one thread per column: strides 8, 4, 2, 1 over the 16 sums
+            float q[16];
 #pragma unroll
-            for (int k = 0; k < KR; ++k) cur[k] = nxt[k];
+            for (int gg = 0; gg < 16; ++gg) q[gg] = sm[gg][tid + (tid >> 3)];
+#pragma unroll
+            for (int st = 8; st >= 1; st >>= 1)
+#pragma unroll
+                for (int ll = 0; ll < st; ++ll) q[ll] = q[ll] + q[ll + st];
+            smean[tid + (tid >> 3)] = q[0] / (float)f;
         }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m[j] = smean[l * 9 + j];
+        if (tid < 64) {                          // this slab's share of mean.mean
+            const float mm = chain8(m, m);
+            const float v = tree32(live ? mm : 0.0f);
+            if (tid == 0) part_mm[(size_t)t * nslabs + slab] = v;
+        }
+    };
+
+    // x.mean of the run's last frame, still packed in `buf`, against the mean slab just finished
+    auto tail = [&](const RawChunk<bf16_t> (&buf)[KR], const int t) {
+        float am[KR];
+#pragma unroll
+        for (int k = 0; k < KR; ++k) {
+            float b[8];
+            unpack(buf[k], b);
+            const float vam = chain8(b, m);
+            am[k] = live ? vam : 0.0f;
+        }
+        mean_products(am, t, true);
+    };
+
+    {
+        const char* const b0 = fbase + (size_t)(t0 > 0 ? t0 - 1 : t0) * frame_bytes;
+        const char* const b1 = fbase + (size_t)t0 * frame_bytes;
+#pragma unroll
+        for (int k = 0; k < KR; ++k) A[k].q = load_stream(reinterpret_cast<const uint4*>(b0 + off[k]));
+#pragma unroll
+        for (int k = 0; k < KR; ++k) B[k].q = load_stream(reinterpret_cast<const uint4*>(b1 + off[k]));
+    }
+    int t = t0;
+    for (; t + 1 < t1; t += 2) {
+        step(A, B, t);                           // prev = A, curr = B; A is refilled with frame t+1
+        step(B, A, t + 1);
+    }
+    if (t < t1) {
+        step(A, B, t);
+        tail(B, t);
+    } else {
+        tail(A, t1 - 1);
     }
 }
 
@@ -533,12 +572,18 @@ int launch_prune_tokens(const TokArgs& a) {
         ranges = ranges > a.n ? a.n : ranges;
         const dim3 grid(slabs * ranges), block(kSlabThreads);
         TimedLaunch tl(kFrameSlab, st);
-        if (a.f <= 144)
-            hipLaunchKernelGGL(frame_slab_kernel<9>, grid, block, 0, st, (const bf16_t*)a.feats, a.n, a.f, a.d, slabs,
-                               ranges, ws.aa, ws.am, ws.ab, ws.part_mm);
-        else
-            hipLaunchKernelGGL(frame_slab_kernel<13>, grid, block, 0, st, (const bf16_t*)a.feats, a.n, a.f, a.d, slabs,
-                               ranges, ws.aa, ws.am, ws.ab, ws.part_mm);
+        switch ((a.f + 15) / 16) {
+#define SHARPV_SLAB_CASE(KR)                                                                                     \
+    case KR:                                                                                                     \
+        hipLaunchKernelGGL(frame_slab_kernel<KR>, grid, block, 0, st, (const bf16_t*)a.feats, a.n, a.f, a.d,     \
+                           slabs, ranges, ws.aa, ws.am, ws.ab, ws.part_mm);                                      \
+        break;
+            SHARPV_SLAB_CASE(1) SHARPV_SLAB_CASE(2) SHARPV_SLAB_CASE(3) SHARPV_SLAB_CASE(4) SHARPV_SLAB_CASE(5)
+            SHARPV_SLAB_CASE(6) SHARPV_SLAB_CASE(7) SHARPV_SLAB_CASE(8) SHARPV_SLAB_CASE(9) SHARPV_SLAB_CASE(10)
+            SHARPV_SLAB_CASE(11) SHARPV_SLAB_CASE(12) SHARPV_SLAB_CASE(13)
+#undef SHARPV_SLAB_CASE
+            default: return SHARPV_ERR_SHAPE;    // tok_uses_slab admits f <= 208 only
+        }
     } else {
         {
             TimedLaunch tl(kFrameMean, st);

@@ -101,8 +101,10 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
     const int g = tid >> 5;
     const int slab = blockIdx.x % nslabs;
     const int range = blockIdx.x / nslabs;
-    const int t0 = (int)((long long)range * n / ranges);
-    const int t1 = (int)((long long)(range + 1) * n / ranges);
+    // runs of n / ranges frames, the first n % ranges of them one frame longer (ranges <= n)
+    const int run_len = n / ranges, run_extra = n % ranges;
+    const int t0 = range * run_len + (range < run_extra ? range : run_extra);
+    const int t1 = t0 + run_len + (range < run_extra ? 1 : 0);
     if (t0 >= t1) return;
     const int nchunks = d / kChunk;
     const int c = slab * kBlockChunks + l;
@@ -329,25 +331,68 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
                                                             int nparts, size_t part_stride,
                                                             const int32_t* __restrict__ frame_offsets, int B,
                                                             int f, int d, float w, int mode, float Kthr, int min_keep,
+                                                            int tpp,   // threads per copy of the frame (multiple of 64, >= f)
                                                             int32_t* __restrict__ local_idx,
                                                             int32_t* __restrict__ out_counts,
                                                             float* __restrict__ out_scores,
                                                             float* __restrict__ out_ratio) {
-    __shared__ float sI[1024];
+    __shared__ unsigned long long sKey[1024];    // (score as an ordered integer, inverted token index)
     __shared__ float sTT[1024];
     __shared__ float sblk[256];
     __shared__ float s_mm;
     __shared__ int s_first;
     __shared__ int s_k;
     __shared__ int wave_cnt[16];
+    __shared__ int sRank[1024];
 
+    // The workgroup holds blockDim.x / tpp copies of the frame's threads ("parts", whole wavefronts):
+    // part 0 owns the tokens, the other parts only take a share of the ranking loop.
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int nthreads = blockDim.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int part = tid / tpp;
+    const int parts = nthreads / tpp;
     const int nchunks = d / kChunk;
     const int nblocks = (nchunks + kBlockChunks - 1) / kBlockChunks;
+
+    // Inner-product shares of this thread's token, summed in ascending block order (a single share
+    // when the rows were summed whole).  The loads come first and in batches of 16 shares x 4 arrays,
+    // so that their latency overlaps the mean.mean and first-frame work below; indices are clamped
+    // (no load under a predicate) and all four arrays are read whether or not the frame turns out to
+    // be a first frame (x.x_prev of frame 0 is never written and never used).
+    const int i = tid - part * tpp;
+    const bool owner = part == 0 && i < f;
+    const size_t r = (size_t)t * f + (i < f ? i : f - 1);
+    const size_t rprev = t > 0 ? r - f : r;
+    float xx = 0.0f, xm = 0.0f, xp = 0.0f, pp = 0.0f;
+    if (nparts == 1 && part == 0) {
+        xx = aa[r];
+        xm = am[r];
+        xp = ab[r];
+        pp = aa[rprev];
+    }
+    for (int s0 = 0; nparts > 1 && part == 0 && s0 < nparts; s0 += 16) {
+        float va[16], vm[16], vb[16], vp[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int sb = s0 + k < nparts ? s0 + k : nparts - 1;
+            const size_t o = (size_t)sb * part_stride;
+            va[k] = aa[o + r];
+            vm[k] = am[o + r];
+            vb[k] = ab[o + r];
+            vp[k] = aa[o + rprev];
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (s0 + k < nparts) {
+                xx = xx + va[k];
+                xm = xm + vm[k];
+                xp = xp + vb[k];
+                pp = pp + vp[k];
+            }
+    }
 
     // mean.mean in the common order: one half-wavefront per 256-element block (or the per-slab
     // shares left by the fused kernel)
@@ -384,59 +429,17 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
     const bool first = s_first != 0 || t == 0;
 
     // Eq.1-4 per token
-    const int i = tid;
     float score = 0.0f;
-    if (i < f) {
-        const size_t r = (size_t)t * f + i;
-        // block shares added in ascending block order (a single share when the rows were summed whole);
-        // the loads of eight shares are issued together (index clamped, so none sits under a predicate)
-        float xx = 0.0f, xm = 0.0f, xp = 0.0f, pp = 0.0f;
-        if (nparts == 1) {
-            xx = aa[r]; xm = am[r];
-            if (!first) { xp = ab[r]; pp = aa[r - f]; }
-        } else if (first) {
-            for (int s0 = 0; s0 < nparts; s0 += 8) {
-                float va[8], vm[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int sb = s0 + k < nparts ? s0 + k : nparts - 1;
-                    const size_t o = (size_t)sb * part_stride + r;
-                    va[k] = aa[o];
-                    vm[k] = am[o];
-                }
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (s0 + k < nparts) {
-                        xx = xx + va[k];
-                        xm = xm + vm[k];
-                    }
-            }
-        } else {
-            for (int s0 = 0; s0 < nparts; s0 += 8) {
-                float va[8], vm[8], vb[8], vp[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int sb = s0 + k < nparts ? s0 + k : nparts - 1;
-                    const size_t o = (size_t)sb * part_stride + r;
-                    va[k] = aa[o];
-                    vm[k] = am[o];
-                    vb[k] = ab[o];
-                    vp[k] = aa[o - f];
-                }
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (s0 + k < nparts) {
-                        xx = xx + va[k];
-                        xm = xm + vm[k];
-                        xp = xp + vb[k];
-                        pp = pp + vp[k];
-                    }
-            }
-        }
+    if (owner) {
         const float S = dissim_from_dots(xm, xx, mm);                        // Eq.2
         const float T = first ? S : dissim_from_dots(xp, xx, pp);            // Eq.3 (Eq.6 on a first frame)
         score = __builtin_fmaf(w, S, T);                                     // Eq.4
-        sI[i] = score;
+        // Ranking key: the float's bits mapped to an unsigned integer of the same order (inputs are
+        // finite, and adding +0 folds -0 into +0 so that equal scores give equal keys), the inverted
+        // index below it: key_j > key_i  <=>  token j is ahead of token i.
+        const uint32_t ub = __float_as_uint(score + 0.0f);
+        const uint32_t ord = (ub & 0x80000000u) ? ~ub : (ub | 0x80000000u);
+        sKey[i] = ((unsigned long long)ord << 32) | (uint32_t)~(uint32_t)i;
         sTT[i] = T * T;
         if (out_scores != nullptr) out_scores[r] = score;
     }
@@ -462,28 +465,31 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
     }
     __syncthreads();
 
-    // top-k by counting: token i is kept iff fewer than k tokens are ahead of it
-    // (higher score, or the same score and a lower index)
-    int keep = 0;
-    if (i < f) {
-        if (mode == 0) {
-            const int k = s_k;
-            int rank = 0;
-            for (int j = 0; j < f; ++j) {
-                const float v = sI[j];
-                rank += (v > score) || (v == score && j < i);
-            }
-            keep = rank < k;
-        } else {
-            keep = score >= Kthr;
-        }
+    // top-k by counting: token i is kept iff fewer than k tokens are ahead of it (higher score, or
+    // the same score and a lower index).  Each part counts over its slice of the frame.
+    int rank = 0;
+    if (mode == 0 && i < f) {
+        const unsigned long long key = sKey[i];
+        const int len = (f + parts - 1) / parts;
+        const int j0 = part * len;
+        const int j1 = j0 + len < f ? j0 + len : f;
+#pragma unroll 8
+        for (int j = j0; j < j1; ++j) rank += sKey[j] > key;
     }
+    if (parts > 1) {
+        sRank[tid] = rank;
+        __syncthreads();
+        if (part == 0)
+            for (int q = 1; q < parts; ++q) rank += sRank[q * tpp + i];
+    }
+    int keep = 0;
+    if (owner) keep = mode == 0 ? rank < s_k : score >= Kthr;
     const unsigned long long bal = __ballot(keep != 0);
     const int before = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    if (lane == 0 && part == 0) wave_cnt[wave] = __popcll(bal);
     __syncthreads();
     int base = 0, total = 0;
-    for (int q = 0; q < (nthreads >> 6); ++q) {
+    for (int q = 0; q < (tpp >> 6); ++q) {
         const int cq = wave_cnt[q];
         base += q < wave ? cq : 0;
         total += cq;
@@ -513,24 +519,66 @@ __global__ __launch_bounds__(1024) void count_scan_kernel(const int32_t* __restr
 
 // ---------------------------------------------------------------------------- compaction
 // One wavefront per kept row j of the compacted stream: its frame is found by bisection of the
-// offsets (staged in LDS when they fit), its source row from the frame's kept list;
-// out_feats[j] = feats[out_idx[j]].
+// offsets, its source row from the frame's kept list; out_feats[j] = feats[out_idx[j]].
+// Up to kOffsetsInLds - 1 frames every workgroup builds the offsets itself from the per-frame counts
+// (an exclusive scan in LDS; workgroup 0 also writes them out), which saves the scan kernel's launch;
+// longer batches get the offsets from count_scan (counts == nullptr).
 constexpr int kOffsetsInLds = 4096;
 __global__ __launch_bounds__(256) void token_gather_kernel(const char* __restrict__ feats, int row_bytes, int n, int f,
-                                                           const int32_t* __restrict__ offsets,
+                                                           const int32_t* __restrict__ counts,
+                                                           int32_t* __restrict__ offsets,
                                                            const int32_t* __restrict__ local_idx,
                                                            int32_t* __restrict__ out_idx, char* __restrict__ out_feats) {
     __shared__ int soff[kOffsetsInLds];
-    const int lane = threadIdx.x & 63;
-    const int total = offsets[n];
-    if ((int)blockIdx.x * 4 >= total) return;
-    const bool staged = n + 1 <= kOffsetsInLds;
+    __shared__ int wave_tot[4];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const bool staged = counts != nullptr;       // host guarantees n + 1 <= kOffsetsInLds in that case
+    int total;
     if (staged) {
-        for (int i = threadIdx.x; i <= n; i += 256) soff[i] = offsets[i];
+        // thread tid owns frames [lo, hi); coalesced enough for the few KB involved
+        const int seg = (n + 255) / 256;
+        const int lo = tid * seg < n ? tid * seg : n;
+        const int hi = lo + seg < n ? lo + seg : n;
+        int sum = 0;
+        for (int j = lo; j < hi; ++j) {
+            const int c = counts[j];
+            soff[j] = c;
+            sum += c;
+        }
+        int incl = sum;
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) {
+            const int u = __shfl_up(incl, sft);
+            if (lane >= sft) incl += u;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
+        int before = 0, all = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            before += q < wave ? wave_tot[q] : 0;
+            all += wave_tot[q];
+        }
+        total = all;
+        int run = before + incl - sum;           // exclusive prefix of this thread's frames
+        for (int j = lo; j < hi; ++j) {
+            const int c = soff[j];
+            soff[j] = run;
+            if (blockIdx.x == 0) offsets[j] = run;
+            run += c;
+        }
+        if (tid == 255) {
+            soff[n] = total;
+            if (blockIdx.x == 0) offsets[n] = total;
+        }
+        __syncthreads();
+    } else {
+        total = offsets[n];
     }
     const int units = row_bytes / 16;
-    for (int j = blockIdx.x * 4 + (threadIdx.x >> 6); j < total; j += gridDim.x * 4) {
+    for (int j = blockIdx.x * 4 + wave; j < total; j += gridDim.x * 4) {
         int lo = 0, hi = n;                  // offsets[lo] <= j < offsets[hi]
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
@@ -607,27 +655,30 @@ int launch_prune_tokens(const TokArgs& a) {
 
     {
         TimedLaunch tl(kFrameSelect, st);
-        const int threads = (a.f + 63) / 64 * 64;
-        hipLaunchKernelGGL(frame_select_kernel, dim3(a.n), dim3(threads), 0, st,
+        const int tpp = (a.f + 63) / 64 * 64;
+        const int parts = 1024 / tpp;            // >= 1 since f <= 1024
+        hipLaunchKernelGGL(frame_select_kernel, dim3(a.n), dim3(tpp * parts), 0, st,
                            fused ? (const float*)nullptr : (const float*)ws.mean, (const float*)ws.part_mm,
                            (const float*)ws.aa, (const float*)ws.am, (const float*)ws.ab, ws.nparts, (size_t)n_rows,
-                           a.frame_offsets, a.B, a.f, a.d, a.w, a.mode, a.K, a.min_keep, ws.local_idx, a.out_counts,
+                           a.frame_offsets, a.B, a.f, a.d, a.w, a.mode, a.K, a.min_keep, tpp, ws.local_idx, a.out_counts,
                            a.out_scores, a.out_ratio);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
 
-    {
+    const bool self_scan = a.n + 1 <= kOffsetsInLds;
+    if (!self_scan) {
         TimedLaunch tl(kCountScan, st);
         hipLaunchKernelGGL(count_scan_kernel, dim3(1), dim3(1024), 0, st, (const int32_t*)a.out_counts, a.n,
                            a.out_offsets);
+        if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
     }
-    if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
 
     {
         TimedLaunch tl(kTokenGather, st);
         const int want = (n_rows + 3) / 4;
         hipLaunchKernelGGL(token_gather_kernel, dim3(want < 2048 ? want : 2048), dim3(256), 0, st,
-                           (const char*)a.feats, (int)(a.d * esz), a.n, a.f, (const int32_t*)a.out_offsets,
+                           (const char*)a.feats, (int)(a.d * esz), a.n, a.f,
+                           self_scan ? (const int32_t*)a.out_counts : (const int32_t*)nullptr, a.out_offsets,
                            (const int32_t*)ws.local_idx, a.out_idx, (char*)a.out_feats);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;

@@ -147,6 +147,14 @@ def small_video(seed, n, f, d, dtype, rho=0.8, cuts=()):
     (4, 65, 264, wl.F32),         # one block + one chunk
     (7, 100, 520, wl.BF16),
     (40, 50, 1024, wl.F32),
+    (3, 208, 256, wl.BF16),       # the tallest frame the fused kernel takes, all rows of every thread inside
+    (3, 209, 256, wl.BF16),       # one row more: the two-kernel path
+    (4, 17, 512, wl.BF16),        # two rows per thread, the second almost empty
+    (9, 48, 264, wl.BF16),        # three rows per thread (odd), a second slab of one chunk
+    (5, 160, 2056, wl.BF16),      # ten rows per thread (two rows left over after the four-row trees)
+    (11, 112, 768, wl.BF16),      # seven rows per thread (three left over)
+    (4100, 3, 16, wl.BF16),       # more frames than the compaction stages offsets for
+    (5000, 4, 8, wl.F32),
 ])
 def test_prune_tokens_shapes(n, f, d, dtype):
     tok = small_video(500 + n * 7 + f, n, f, d, dtype, cuts=(n // 2,) if n > 2 else ())

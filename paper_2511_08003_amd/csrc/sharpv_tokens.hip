@@ -85,27 +85,17 @@ constexpr int kSlabThreads = 512;   // 16 row groups x 32 lanes
 // Every lane loads from a valid address (row and chunk indices are clamped) so that no load sits
 // under a per-lane predicate; lanes past the end of a row contribute zeros to the trees, and the
 // one row per thread that may lie past the frame is zeroed before it enters the column sums.
+constexpr int kSlabRowLds = kBlockElems + kBlockChunks;   // a 256-column row in LDS plus its pad words
+
 template <int KR>
-__global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* __restrict__ feats, int n, int f, int d,
-                                                                  int nslabs, int ranges,
-                                                                  float* __restrict__ part_aa,   // [nslabs][n*f]
-                                                                  float* __restrict__ part_am,
-                                                                  float* __restrict__ part_ab,
-                                                                  float* __restrict__ part_mm) { // [n][nslabs]
-    // column c sits at index c + c/8 (one pad word per chunk of 8), which spreads a lane's 8
-    // consecutive words and the other lanes' over distinct LDS banks
-    __shared__ float sm[16][kBlockElems + kBlockChunks];   // column sums of classes g and g+16 already added
-    __shared__ float smean[kBlockElems + kBlockChunks];
+__device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const int n, const int f, const int d,
+                                         const int nslabs, const int slab, const int t0, const int t1,
+                                         float* __restrict__ part_aa, float* __restrict__ part_am,
+                                         float* __restrict__ part_ab, float* __restrict__ part_mm,
+                                         float (&sm)[16][kSlabRowLds], float (&smean)[kSlabRowLds]) {
     const int tid = threadIdx.x;
     const int l = tid & 31;
     const int g = tid >> 5;
-    const int slab = blockIdx.x % nslabs;
-    const int range = blockIdx.x / nslabs;
-    // runs of n / ranges frames, the first n % ranges of them one frame longer (ranges <= n)
-    const int run_len = n / ranges, run_extra = n % ranges;
-    const int t0 = range * run_len + (range < run_extra ? range : run_extra);
-    const int t1 = t0 + run_len + (range < run_extra ? 1 : 0);
-    if (t0 >= t1) return;
     const int nchunks = d / kChunk;
     const int c = slab * kBlockChunks + l;
     const bool live = c < nchunks;
@@ -274,6 +264,34 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
         tail(B, t);
     } else {
         tail(A, t1 - 1);
+    }
+}
+
+// The (slab, frame) pairs, slab-major, are dealt out in equal contiguous runs, one per workgroup
+// (about one workgroup per compute unit): a run that crosses into the next slab continues there at
+// frame 0, which needs no predecessor, so every workgroup reads at most one frame slab beyond its
+// own share.
+template <int KR>
+__global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* __restrict__ feats, int n, int f, int d,
+                                                                  int nslabs, int run_len, int run_extra,
+                                                                  float* __restrict__ part_aa,   // [nslabs][n*f]
+                                                                  float* __restrict__ part_am,
+                                                                  float* __restrict__ part_ab,
+                                                                  float* __restrict__ part_mm) { // [n][nslabs]
+    // column c sits at index c + c/8 (one pad word per chunk of 8), which spreads a lane's 8
+    // consecutive words and the other lanes' over distinct LDS banks
+    __shared__ float sm[16][kSlabRowLds];        // column sums of classes g and g+16 already added
+    __shared__ float smean[kSlabRowLds];
+    // runs of run_len pairs, the first run_extra of them one pair longer
+    const int w = blockIdx.x;
+    long long u = (long long)w * run_len + (w < run_extra ? w : run_extra);   // nslabs * n may pass 2^31
+    const long long u_end = u + run_len + (w < run_extra ? 1 : 0);
+    while (u < u_end) {
+        const int slab = (int)(u / n);
+        const int t0 = (int)(u - (long long)slab * n);
+        const int t1 = (long long)t0 + (u_end - u) < n ? t0 + (int)(u_end - u) : n;
+        slab_run<KR>(feats, n, f, d, nslabs, slab, t0, t1, part_aa, part_am, part_ab, part_mm, sm, smean);
+        u += t1 - t0;
     }
 }
 
@@ -605,6 +623,18 @@ __global__ __launch_bounds__(256) void token_gather_kernel(const char* __restric
 }
 
 // ---------------------------------------------------------------------------- host side
+static int num_compute_units() {
+    static int cached = 0;                       // per process; devices of one machine are alike
+    if (cached == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        cached = cus;
+    }
+    return cached;
+}
+
 int launch_prune_tokens(const TokArgs& a) {
     hipStream_t st = a.stream;
     TokWorkspace ws = carve_tok_workspace(a.workspace, a.n, a.f, a.d, a.dtype);
@@ -614,17 +644,17 @@ int launch_prune_tokens(const TokArgs& a) {
     const bool fused = tok_uses_slab(a.dtype, a.f);
 
     if (fused) {
-        // one workgroup per (slab, run of frames); about one workgroup per compute unit
-        int ranges = 256 / slabs;
-        ranges = ranges < 1 ? 1 : ranges;
-        ranges = ranges > a.n ? a.n : ranges;
-        const dim3 grid(slabs * ranges), block(kSlabThreads);
+        // equal runs of (slab, frame) pairs, about one workgroup per compute unit
+        const long long pairs = (long long)slabs * a.n;
+        const int wgs = pairs < num_compute_units() ? (int)pairs : num_compute_units();
+        const int run_len = (int)(pairs / wgs), run_extra = (int)(pairs % wgs);   // run_len <= n * slabs / 1 fits: n < 2^31
+        const dim3 grid(wgs), block(kSlabThreads);
         TimedLaunch tl(kFrameSlab, st);
         switch ((a.f + 15) / 16) {
 #define SHARPV_SLAB_CASE(KR)                                                                                     \
     case KR:                                                                                                     \
         hipLaunchKernelGGL(frame_slab_kernel<KR>, grid, block, 0, st, (const bf16_t*)a.feats, a.n, a.f, a.d,     \
-                           slabs, ranges, ws.aa, ws.am, ws.ab, ws.part_mm);                                      \
+                           slabs, run_len, run_extra, ws.aa, ws.am, ws.ab, ws.part_mm);                                      \
         break;
             SHARPV_SLAB_CASE(1) SHARPV_SLAB_CASE(2) SHARPV_SLAB_CASE(3) SHARPV_SLAB_CASE(4) SHARPV_SLAB_CASE(5)
             SHARPV_SLAB_CASE(6) SHARPV_SLAB_CASE(7) SHARPV_SLAB_CASE(8) SHARPV_SLAB_CASE(9) SHARPV_SLAB_CASE(10)

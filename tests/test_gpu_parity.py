@@ -306,3 +306,50 @@ def test_error_codes_with_real_buffers():
     plan2 = sharpv.TokensPlan(2, 16, 64, sharpv.default_params())
     plan2.params = p2
     assert plan2.run(x) == 4
+
+
+# ----------------------------------------------------------------------------- measurement aids and event timing
+@pytest.mark.parametrize("nbytes", [16, 48, 8192, 16 * 1000003, 64 << 20])
+def test_stream_copy_and_read(nbytes):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(nbytes)
+    src = torch.randint(-2**31, 2**31 - 1, (nbytes // 4,), dtype=torch.int32, device="cuda", generator=g)
+    dst = torch.full((nbytes // 4 + 4,), 7, dtype=torch.int32, device="cuda")
+    sharpv.stream_copy(dst, src)
+    sink = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+    sharpv.stream_read(src, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[: nbytes // 4], src)
+    assert torch.all(dst[nbytes // 4:] == 7)         # nothing written past the end
+    assert int(sink[0]) == -5                        # the read leaves no trace
+    L = sharpv.load()
+    assert L.sharpv_stream_copy(dst.data_ptr(), src.data_ptr(), 24, None) == 2       # not a multiple of 16
+    assert L.sharpv_stream_copy(dst.data_ptr() + 4, src.data_ptr(), 16, None) == 2   # misaligned
+    assert L.sharpv_stream_read(None, 16, sink.data_ptr(), None) == 1
+
+
+def test_event_timing_counts_launches():
+    tok = small_video(801, 4, 64, 512, wl.BF16)
+    x = dev(tok.feats, wl.BF16)
+    sharpv.timing_enable(64)
+    try:
+        for _ in range(3):
+            sharpv.prune_tokens(x)
+        torch.cuda.synchronize()
+        for name in ("frame_slab", "frame_select", "token_gather"):
+            n, ms = sharpv.timing_read(name)
+            assert n == 3 and 0.0 < ms < 1000.0
+        assert sharpv.timing_read("kv_cosine") == (0, 0.0)
+        with pytest.raises(RuntimeError):
+            sharpv.timing_read("no_such_kernel")
+    finally:
+        sharpv.timing_disable()
+    # disabled again: launches are no longer recorded, results unchanged
+    a = sharpv.prune_tokens(x)["idx"].cpu().numpy()
+    sharpv.timing_enable(1)                          # a pool smaller than the launches of one call
+    try:
+        b = sharpv.prune_tokens(x)["idx"].cpu().numpy()
+        torch.cuda.synchronize()
+    finally:
+        sharpv.timing_disable()
+    np.testing.assert_array_equal(a, b)

@@ -51,6 +51,9 @@ def lib() -> C.CDLL:
         L.sharpv_canon_prune_kv.restype = C.c_long
         L.sharpv_canon_prune_kv.argtypes = [vp, vp, vp, vp, C.c_int, ip, ip, ip, C.c_int, C.c_int, C.c_int, C.c_int,
                                             C.c_float, C.c_int, fp, fp, ip, ip, vp, vp]
+        L.sharpv_canon_rope_reencode.restype = C.c_int
+        L.sharpv_canon_rope_reencode.argtypes = [vp, C.c_int, ip, C.c_long, ip, C.c_int, C.c_int, C.c_int, fp, fp,
+                                                 C.c_int, C.c_int]
         _lib = L
     return _lib
 
@@ -158,3 +161,21 @@ def prune_kv(hidden: np.ndarray, orig: np.ndarray, Kc: Optional[np.ndarray], Vc:
         res["K_out"] = K_out.reshape(-1)[:H * tot * D].reshape(H, tot, D).copy()
         res["V_out"] = V_out.reshape(-1)[:H * tot * D].reshape(H, tot, D).copy()
     return res
+
+
+def rope_reencode(K_kept: np.ndarray, dtype: int, idx: np.ndarray, seq_offsets: np.ndarray,
+                  cos_tab: np.ndarray, sin_tab: np.ndarray, layout: int = 0) -> np.ndarray:
+    """Float32 rotary re-encoding of the kept K rows [H, S_kept, D]; returns a new storage array."""
+    K = _storage(K_kept, dtype).copy()
+    H, n_kept, D = K.shape
+    ct = np.ascontiguousarray(cos_tab, np.float32)
+    st = np.ascontiguousarray(sin_tab, np.float32)
+    assert ct.shape == st.shape and ct.shape[1] == D // 2
+    so = np.ascontiguousarray(seq_offsets, np.int32)
+    ix = np.ascontiguousarray(idx, np.int32)
+    assert len(ix) == n_kept
+    rc = lib().sharpv_canon_rope_reencode(_vp(K), dtype, _ip(ix), n_kept, _ip(so), len(so) - 1, H, D,
+                                          _fp(ct), _fp(st), ct.shape[0], layout)
+    if rc != 0:
+        raise ValueError("sharpv_canon_rope_reencode: bad argument or table too short")
+    return K

@@ -33,6 +33,9 @@
  *   r_t             = clamp(sqrtf(SUM32(T_i * T_i)) / (2 * sqrtf((float) f)), 0, 1)   (Eq.5/6)
  *   k_t             = clamp((int) floorf(r_t * (float) f + 0.5f), min_keep, f)
  *
+ *   rotary re-encoding of a kept K row (Sec. 4.1, Implementation Details), pair (x, y), table entries c, s:
+ *       x' = fmaf(x, c, y * s),  y' = fmaf(y, c, -(x * s)),  rounded once to the storage type
+ *
  * bf16 inputs are widened exactly (bits << 16).  sqrtf and "/" are correctly rounded.
  * Identical rows give xx == yy == xy and sqrtf(xx*xx) == xx, hence cos == 1 and Dissim == 0
  * exactly (a repeated frame keeps nothing).  Inputs must be finite with xx*yy inside the
@@ -281,4 +284,60 @@ long sharpv_canon_prune_kv(const void* hidden, const void* orig, const void* Kc,
     }
     free(keep);
     return n_kept;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Rotary re-encoding of the compacted K cache (Sec. 4.1, Implementation Details), in place.
+ *
+ * K_rows [H][n_kept][D] are the kept K rows in stream order, out_idx their packed positions.  The
+ * j-th kept row of a sequence that sat at position p of that sequence is turned back by
+ * delta = p - j steps:  with c = cos_tab[delta][i], s = sin_tab[delta][i] (tables [rope_len][D/2] from the
+ * caller) and (x, y) the i-th pair of the row (layout 0: elements i and i + D/2; layout 1: 2i and 2i+1)
+ *     x' = fmaf(x, c, y * s)        y' = fmaf(y, c, -(x * s))
+ * in float32 (the two products y*s and x*s rounded on their own), then rounded to the storage type
+ * (bf16: to nearest, ties to even).  Returns 0, or -1 for a bad argument or a delta >= rope_len.
+ */
+static uint16_t f32_to_bf16_rne(float v) {
+    uint32_t u;
+    memcpy(&u, &v, 4);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int sharpv_canon_rope_reencode(void* K_rows, int dtype, const int32_t* out_idx, long n_kept,
+                               const int32_t* seq_offsets, int B, int H, int D,
+                               const float* cos_tab, const float* sin_tab, int rope_len, int layout) {
+    if (!K_rows || !out_idx || !seq_offsets || !cos_tab || !sin_tab || B < 1 || D < 2 || (D & 1)) return -1;
+    if (layout != 0 && layout != 1) return -1;
+    const int half = D / 2;
+    int seq = 0, rank = 0;
+    for (long j = 0; j < n_kept; ++j) {
+        const int s = out_idx[j];
+        while (seq + 1 < B && s >= seq_offsets[seq + 1]) { ++seq; rank = 0; }
+        const int delta = (s - seq_offsets[seq]) - rank;
+        if (delta < 0 || delta >= rope_len) return -1;
+        const float* ct = cos_tab + (size_t)delta * half;
+        const float* st = sin_tab + (size_t)delta * half;
+        for (int h = 0; h < H; ++h) {
+            const size_t row = ((size_t)h * (size_t)n_kept + (size_t)j) * (size_t)D;
+            for (int i = 0; i < half; ++i) {
+                const size_t ia = row + (size_t)(layout == 0 ? i : 2 * i);
+                const size_t ib = row + (size_t)(layout == 0 ? i + half : 2 * i + 1);
+                float x, y;
+                if (dtype == CANON_F32) { x = ((float*)K_rows)[ia]; y = ((float*)K_rows)[ib]; }
+                else {
+                    uint32_t ux = (uint32_t)((uint16_t*)K_rows)[ia] << 16, uy = (uint32_t)((uint16_t*)K_rows)[ib] << 16;
+                    memcpy(&x, &ux, 4); memcpy(&y, &uy, 4);
+                }
+                const float ys = y * st[i];
+                const float xs = x * st[i];
+                const float xn = fmaf(x, ct[i], ys);
+                const float yn = fmaf(y, ct[i], -xs);
+                if (dtype == CANON_F32) { ((float*)K_rows)[ia] = xn; ((float*)K_rows)[ib] = yn; }
+                else { ((uint16_t*)K_rows)[ia] = f32_to_bf16_rne(xn); ((uint16_t*)K_rows)[ib] = f32_to_bf16_rne(yn); }
+            }
+        }
+        ++rank;
+    }
+    return 0;
 }

@@ -17,7 +17,10 @@ Readings taken where the paper is silent (each is listed with its reason in the 
   * a zero-norm vector has cosine 0 to everything;
   * top-k ties go to the lowest token index, kept tokens stay in stream order;
   * Eq.7 is applied per visual token (kv_mode 0) or to the mean over a sequence's visual
-    tokens (kv_mode 1); non-visual positions are always kept; "< M" is strict.
+    tokens (kv_mode 1); non-visual positions are always kept; "< M" is strict;
+  * the positional re-encoding of Sec. 4.1 (Implementation Details) is read as: every kept K
+    row gets the rotary embedding of its new place in the compacted cache; the paper names no
+    rotary convention, so frequencies (as cos/sin tables) and pairing come from the caller.
 
 Pins: tests/test_oracle_pins.py (closed forms, invariants, brute force, library routines).
 No function here is "parity unpinned".
@@ -184,6 +187,46 @@ def prune_kv(hidden: np.ndarray, orig: np.ndarray, Kc: np.ndarray, Vc: np.ndarra
     idx = np.nonzero(keep)[0].astype(np.int32)
     return {"cos": cos, "mean_cos": mean_cos, "idx": idx, "counts": counts,
             "K_out": np.asarray(Kc)[:, idx, :], "V_out": np.asarray(Vc)[:, idx, :]}
+
+
+# ----------------------------------------------------------------------------- rotary re-encoding
+def rope_reencode(K_kept: np.ndarray, dtype: int, idx: np.ndarray, seq_offsets: np.ndarray,
+                  cos_tab: np.ndarray, sin_tab: np.ndarray, layout: int = 0) -> np.ndarray:
+    """Positional re-encoding of the compacted K cache (Sec. 4.1, Implementation Details: the
+    positional embedding is re-encoded during intra-LLM pruning).
+
+    K_kept [H, S_kept, D] holds the kept K rows in stream order, idx their packed positions.
+    A row that sat at position p of its sequence and is now the j-th kept row of that sequence
+    carries a rotary embedding for p and needs the one for j: every pair (x, y) of the row is
+    turned back by delta = p - j steps of its frequency,
+        x' = x cos(delta*theta_i) + y sin(delta*theta_i),   y' = y cos(delta*theta_i) - x sin(delta*theta_i).
+    The caller's model fixes the frequencies and hands over cos_tab / sin_tab [L, D/2] with
+    row delta = cos / sin of delta*theta_i (L > every delta).  layout 0 pairs element i with
+    i + D/2 (the "rotate half" convention), layout 1 pairs 2i with 2i+1.
+    Returns float64 [H, S_kept, D] (not rounded back to the storage type)."""
+    K = widen(K_kept, dtype)
+    H, n_kept, D = K.shape
+    half = D // 2
+    so = np.asarray(seq_offsets, dtype=np.int64)
+    idx = np.asarray(idx, dtype=np.int64)
+    out = np.empty_like(K)
+    ia = np.arange(half) if layout == 0 else 2 * np.arange(half)
+    ib = ia + half if layout == 0 else ia + 1
+    rank_in_seq = 0
+    seq = 0
+    for j in range(n_kept):
+        s = int(idx[j])
+        while s >= so[seq + 1]:
+            seq += 1
+            rank_in_seq = 0
+        delta = (s - int(so[seq])) - rank_in_seq
+        c = np.asarray(cos_tab[delta], dtype=np.float64)
+        sn = np.asarray(sin_tab[delta], dtype=np.float64)
+        x, y = K[:, j, ia], K[:, j, ib]
+        out[:, j, ia] = x * c + y * sn
+        out[:, j, ib] = y * c - x * sn
+        rank_in_seq += 1
+    return out
 
 
 # ----------------------------------------------------------------------------- retention figures

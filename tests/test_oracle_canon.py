@@ -271,3 +271,62 @@ def test_prune_kv_extremes_ragged_bf16():
     assert len(canon.prune_kv(*args, M=1.5)["idx"]) == 14
     kept = [len(canon.prune_kv(*args, M=m)["idx"]) for m in (-1.0, -0.5, 0.0, 0.2, 0.99, 1.0, 1.01)]
     assert all(y <= x for x, y in zip(kept, kept[1:]))
+
+
+# ----------------------------------------------------------------------------- rotary re-encoding
+def test_rope_reencode_exact_cases():
+    rng = np.random.default_rng(41)
+    H, D, S = 2, 16, 12
+    K = rng.integers(-20, 21, size=(H, S, D)).astype(np.float32)
+    seq = np.array([0, S])
+    idx = np.array([0, 3, 4, 9, 11])                    # deltas 0, 2, 2, 6, 7
+    L = 8
+    for dtype, store in ((wl.F32, K), (wl.BF16, wl.f32_to_bf16_bits(K))):
+        # delta 0 everywhere: bit-for-bit identity, whatever the tables hold at the other deltas
+        ct = np.full((L, D // 2), 0.37, np.float32); st = np.full((L, D // 2), -0.91, np.float32)
+        ct[0], st[0] = 1.0, 0.0
+        np.testing.assert_array_equal(canon.rope_reencode(store, dtype, np.arange(S), seq, ct, st, 0), store)
+        # quarter turn at every delta > 0 (cos 0, sin 1): x' = y, y' = -x exactly
+        ct[1:], st[1:] = 0.0, 1.0
+        got = wl.storage_to_f32(canon.rope_reencode(store[:, idx], dtype, idx, seq, ct, st, 0), dtype)
+        want = K[:, idx].copy()
+        want[:, 1:, :D // 2], want[:, 1:, D // 2:] = K[:, idx[1:], D // 2:], -K[:, idx[1:], :D // 2]
+        np.testing.assert_array_equal(got, want)
+        got = wl.storage_to_f32(canon.rope_reencode(store[:, idx], dtype, idx, seq, ct, st, 1), dtype)
+        want = K[:, idx].copy()
+        want[:, 1:, 0::2], want[:, 1:, 1::2] = K[:, idx[1:], 1::2], -K[:, idx[1:], 0::2]
+        np.testing.assert_array_equal(got, want)
+        # dyadic table entries per delta and per pair: exact in float32 on small integers (and in bf16: |.| < 256)
+        ct = (rng.integers(-4, 5, size=(L, D // 2)) / 4).astype(np.float32)
+        st = (rng.integers(-4, 5, size=(L, D // 2)) / 4).astype(np.float32)
+        Kq = (np.round(K / 4) * 4).astype(np.float32)   # multiples of 4 keep every result an integer below 256
+        sq = Kq if dtype == wl.F32 else wl.f32_to_bf16_bits(Kq)
+        got = wl.storage_to_f32(canon.rope_reencode(sq[:, idx], dtype, idx, seq, ct, st, 0), dtype)
+        d = idx - np.arange(len(idx))
+        x, y = Kq[:, idx, :D // 2].astype(np.float64), Kq[:, idx, D // 2:].astype(np.float64)
+        np.testing.assert_array_equal(got[:, :, :D // 2], x * ct[d] + y * st[d])
+        np.testing.assert_array_equal(got[:, :, D // 2:], y * ct[d] - x * st[d])
+    with pytest.raises(ValueError):                     # delta 7 needs a table of 8 rows
+        canon.rope_reencode(K[:, idx], wl.F32, idx, seq, ct[:7], st[:7], 0)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_rope_reencode_matches_definition(layout):
+    rng = np.random.default_rng(43 + layout)
+    H, D = 4, 128
+    seq = np.array([0, 300, 700])
+    keep = rng.random(700) < 0.4
+    keep[[0, 299, 300]] = True
+    idx = np.nonzero(keep)[0]
+    theta = 1e6 ** (-2.0 * np.arange(D // 2) / D)
+    ang = np.arange(400)[:, None] * theta[None, :]
+    ct, st = np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+    K = rng.standard_normal((H, 700, D)).astype(np.float32)
+    want = ref.rope_reencode(K[:, idx], wl.F32, idx, seq, ct, st, layout)
+    got = canon.rope_reencode(K[:, idx], wl.F32, idx, seq, ct, st, layout)
+    np.testing.assert_allclose(got, want, rtol=0, atol=4 * 2.0 ** -24 * 8)      # a few float32 ulps at |x| < 8
+    Kb = wl.f32_to_bf16_bits(K)
+    want = ref.rope_reencode(Kb[:, idx], wl.BF16, idx, seq, ct, st, layout)
+    got = wl.storage_to_f32(canon.rope_reencode(Kb[:, idx], wl.BF16, idx, seq, ct, st, layout), wl.BF16)
+    # one rounding to bf16 (8 significant bits: half an ulp <= 2^-8 relative) on top of the float32 arithmetic
+    np.testing.assert_allclose(got, want, rtol=2.0 ** -8 * 1.001, atol=1e-6)

@@ -375,3 +375,75 @@ def test_widen_bf16_is_exact():
 def test_retention_figures():
     r = ref.retention(np.array([10, 30]), 100, kept_kv=50, S=200)
     assert r["VR"] == pytest.approx(0.2) and r["MR"] == pytest.approx(0.25) and r["budget"] == pytest.approx(0.05)
+
+
+# ----------------------------------------------------------------------------- rotary re-encoding of the kept K rows
+def _rope_tables(L, D, base=10000.0):
+    theta = base ** (-2.0 * np.arange(D // 2) / D)
+    ang = np.arange(L)[:, None] * theta[None, :]
+    return theta, np.cos(ang), np.sin(ang)
+
+
+def _rotate_complex(k0, pos, theta, layout):
+    """Textbook rotary embedding via complex numbers: pair (x, y) -> (x + iy) * exp(i * pos * theta)."""
+    D = k0.shape[-1]
+    ia = np.arange(D // 2) if layout == 0 else 2 * np.arange(D // 2)
+    ib = ia + D // 2 if layout == 0 else ia + 1
+    z = (k0[..., ia] + 1j * k0[..., ib]) * np.exp(1j * np.asarray(pos)[..., None] * theta)
+    out = np.empty_like(k0)
+    out[..., ia], out[..., ib] = z.real, z.imag
+    return out
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_rope_reencode_moves_a_row_to_its_new_position(layout):
+    # rows embedded for their old positions come out embedded for their ranks among the kept rows, per sequence
+    rng = np.random.default_rng(31 + layout)
+    H, D = 3, 16
+    seq = np.array([0, 11, 30])                        # two sequences of 11 and 19 positions
+    idx = np.array([0, 1, 4, 9, 10, 11, 13, 14, 22, 29])
+    pos_old = np.array([0, 1, 4, 9, 10, 0, 2, 3, 11, 18])
+    pos_new = np.array([0, 1, 2, 3, 4, 0, 1, 2, 3, 4])
+    theta, ct, st = _rope_tables(32, D)
+    k0 = rng.standard_normal((H, len(idx), D))
+    K_old = _rotate_complex(k0, np.broadcast_to(pos_old, (H, len(idx))), theta, layout)
+    got = ref.rope_reencode(K_old.astype(np.float32), 0, idx, seq, ct, st, layout)
+    want = _rotate_complex(k0, np.broadcast_to(pos_new, (H, len(idx))), theta, layout)
+    np.testing.assert_allclose(got, want, atol=2e-6)
+    # and it is not a no-op: the rows that moved differ from their input
+    moved = pos_old != pos_new
+    assert np.all(np.abs(got[:, moved] - K_old[:, moved]).max(axis=-1) > 1e-3)
+
+
+def test_rope_reencode_identity_norms_batches_and_layouts():
+    rng = np.random.default_rng(37)
+    H, D, S = 2, 8, 20
+    theta, ct, st = _rope_tables(S, D)
+    K = rng.standard_normal((H, S, D)).astype(np.float32)
+    seq = np.array([0, S])
+    # nothing pruned: every delta is 0 and the rows come back unchanged
+    np.testing.assert_array_equal(ref.rope_reencode(K, 0, np.arange(S), seq, ct, st, 0), K.astype(np.float64))
+    # a rotation: the norm of every pair, hence of every row, is preserved
+    idx = np.array([2, 3, 7, 8, 15, 19])
+    out = ref.rope_reencode(K[:, idx], 0, idx, seq, ct, st, 0)
+    np.testing.assert_allclose(np.linalg.norm(out, axis=-1), np.linalg.norm(K[:, idx].astype(np.float64), axis=-1),
+                               rtol=1e-7)
+    # attention logits between re-encoded keys depend on the new distance only: <R(a)q, R(b)k> = <R(a-b)q, k>
+    q = rng.standard_normal(D)
+    for a, b in ((0, 3), (2, 5)):
+        ka = _rotate_complex(K[0, idx[a]].astype(np.float64), 0, theta, 0)       # un-embedded stand-in
+        lhs = _rotate_complex(q, b, theta, 0) @ _rotate_complex(ka, a, theta, 0)
+        rhs = _rotate_complex(q, b - a, theta, 0) @ ka
+        assert lhs == pytest.approx(rhs, rel=1e-9)
+    # a packed batch is the concatenation of its sequences (delta restarts at each sequence)
+    seq2 = np.array([0, 9, S])
+    idx2 = np.array([1, 4, 8, 9, 12, 19])
+    both = ref.rope_reencode(K[:, idx2], 0, idx2, seq2, ct, st, 0)
+    first = ref.rope_reencode(K[:, idx2[:3]], 0, idx2[:3], np.array([0, 9]), ct, st, 0)
+    second = ref.rope_reencode(K[:, idx2[3:]], 0, idx2[3:] - 9, np.array([0, S - 9]), ct, st, 0)
+    np.testing.assert_array_equal(both, np.concatenate([first, second], axis=1))
+    # the two pairings are the same rotation up to a fixed shuffle of the head dimension
+    perm = np.empty(D, dtype=int)
+    perm[0::2], perm[1::2] = np.arange(D // 2), np.arange(D // 2) + D // 2    # interleaved slot <- half-split slot
+    inter = ref.rope_reencode(K[:, idx][:, :, perm], 0, idx, seq, ct, st, 1)
+    np.testing.assert_array_equal(inter, out[:, :, perm])

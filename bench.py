@@ -145,12 +145,38 @@ def main() -> int:
     ms_stage2 = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
     ms_stage2_layer = ms_stage2 / len(layers)
 
+    # ------------------------------------------------------------------ the KV stage with rotary re-encoding of the kept K rows
+    # (same step, sharpv_prune_kv_rope instead of sharpv_prune_kv; reported beside the headline, not in it)
+    theta = 1e6 ** (-2.0 * np.arange(cfg.D // 2) / cfg.D)
+    ang = np.arange(S)[:, None] * theta[None, :]
+    rope_cos = torch.from_numpy(np.cos(ang).astype(np.float32)).to(dev)
+    rope_sin = torch.from_numpy(np.sin(ang).astype(np.float32)).to(dev)
+
+    def stage2_rope(i):
+        rc = kplan.run(hidden[i], orig, Kc[i], Vc[i], int(lay.vis_start[0]), so, vs, vo, layers[i], rope_cos, rope_sin)
+        if rc:
+            raise RuntimeError(sharpv.status_string(rc))
+
+    for i in range(len(layers)):
+        stage2_rope(i)
+    torch.cuda.synchronize()
+    er = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    er[0].record()
+    for _ in range(args.steps):
+        for i in range(len(layers)):
+            stage2_rope(i)
+    er[1].record()
+    torch.cuda.synchronize()
+    ms_rope_layer = er[0].elapsed_time(er[1]) / (args.steps * len(layers))
+
     # ------------------------------------------------------------------ per-kernel durations (events around every launch)
-    launches_per_step = 6 + 3 * len(layers)
+    launches_per_step = 6 + 5 * len(layers)
     n_ceiling = 6
     sharpv.timing_enable(launches_per_step * args.steps + 2 * n_ceiling + 8)
     for _ in range(args.steps):
         step()
+    for i in range(len(layers)):
+        stage2_rope(i)
     # practical HBM ceilings of this device: plain read and plain copy of buffers of the same size
     # class (hidden states of different layers, so nothing is served from cache)
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
@@ -180,7 +206,11 @@ def main() -> int:
     dom = "kv_cosine"
     dom_gbps = bytes_cos / (kern[dom]["avg_us"] * 1e-6) / 1e9
     hid_bytes = hidden[0].numel() * esz
-    for name, b in (("kv_cosine", bytes_cos), ("kv_gather", bytes_gather_avg), ("frame_slab", Nv * row),
+    # re-encoding adds one row of each table (D/2 float32 cos + sin) per kept position
+    bytes_gather_rope_avg = bytes_gather_avg + float(np.mean(kept_kv)) * cfg.D * 4
+    gbps_rope = (bytes_cos + bytes_gather_rope_avg) / (ms_rope_layer * 1e-3) / 1e9
+    for name, b in (("kv_cosine", bytes_cos), ("kv_gather", bytes_gather_avg), ("kv_gather_rope", bytes_gather_rope_avg),
+                    ("frame_slab", Nv * row),
                     ("frame_mean", Nv * row), ("token_dots", Nv * row), ("token_gather", 2 * kept_tokens * row),
                     ("stream_read", hid_bytes), ("stream_copy", 2 * Nv * row)):
         if name in kern:
@@ -217,6 +247,9 @@ def main() -> int:
                    "frac_hbm_peak": round(gbps_stage1 / HBM_PEAK_GBPS, 4)},
         "kv_prune": {"ms_per_layer": round(ms_stage2_layer, 4), "alg_bytes_per_layer": int(bytes_stage2_avg),
                      "GBps": round(gbps_stage2, 1), "frac_hbm_peak": round(gbps_stage2 / HBM_PEAK_GBPS, 4)},
+        "kv_prune_rope": {"ms_per_layer": round(ms_rope_layer, 4),
+                          "alg_bytes_per_layer": int(bytes_cos + bytes_gather_rope_avg), "GBps": round(gbps_rope, 1),
+                          "frac_hbm_peak": round(gbps_rope / HBM_PEAK_GBPS, 4)},
         "tokens_per_s_whole_step": round(Nv / (ms_per_step * 1e-3), 1),
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,

@@ -138,13 +138,45 @@ int sharpv_prune_kv(
     void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Intra-LLM stage with positional re-encoding (Sec. 4.1, Implementation Details: the positional
+ * embedding is re-encoded during intra-LLM pruning).
+ *
+ * Same decisions, outputs and limits as sharpv_prune_kv, except that every kept K row leaves with the
+ * rotary embedding of its NEW place: a row that sat at position p of its sequence and becomes that
+ * sequence's j-th kept row is turned back by delta = p - j steps.  The model's rotary convention stays
+ * with the caller: rope_cos / rope_sin are device tables [rope_len][D/2] of float32 whose row `delta`
+ * holds cos / sin of delta * theta_i (i-th frequency), and rope_layout says which elements form pair i
+ * (SHARPV_ROPE_HALF: i and i + D/2; SHARPV_ROPE_INTERLEAVED: 2i and 2i+1).  Per pair (x, y), in float32:
+ *     x' = fma(x, c, y*s),  y' = fma(y, c, -(x*s)),   rounded once to params->dtype.
+ * V rows are copied unchanged.  Extra limits: D*sizeof(element) a multiple of 32 (a half row is whole
+ * 16-byte pieces), rope_len >= S (no shift can be larger), tables 4-byte aligned and caller-owned.
+ */
+typedef enum { SHARPV_ROPE_HALF = 0, SHARPV_ROPE_INTERLEAVED = 1 } sharpv_rope_layout;
+
+int sharpv_prune_kv_rope(
+    const void* hidden, const void* orig, const void* K, const void* V,
+    int64_t kv_stride_h, int64_t kv_stride_s,
+    const int32_t* seq_offsets, const int32_t* vis_start, const int32_t* vis_offsets,
+    int B, int S, int vis_start0, int n_vis, int d, int H, int D, int layer,
+    const sharpv_params* params,   /* host */
+    int32_t* out_idx, int32_t* out_count,
+    void* K_out, void* V_out, int64_t out_stride_h,
+    float* out_cos, float* out_mean_cos,
+    const float* rope_cos,         /* device [rope_len, D/2] */
+    const float* rope_sin,         /* device [rope_len, D/2] */
+    int rope_len, int rope_layout,
+    void* workspace, size_t workspace_bytes,   /* sized by sharpv_prune_kv_workspace */
+    void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the launch stream (for benchmarks; off by default).
  * While enabled, every kernel launch of the two entry points is bracketed by a pair of events
  * taken from a pool of `max_launches` pairs (launches beyond the pool go untimed).
  * sharpv_timing_read synchronises on the recorded events and returns, for the kernel with the
  * given name, the number of timed launches and their summed duration in milliseconds.
  * Kernel names: "frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
- * "kv_cosine", "kv_mean", "kv_gather", "stream_copy", "stream_read".  Not thread-safe; one device.
+ * "kv_cosine", "kv_mean", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read".  Not thread-safe;
+ * one device.
  */
 int sharpv_timing_enable(int max_launches);     /* creates the pool; resets earlier records */
 int sharpv_timing_disable(void);                /* destroys the pool */

@@ -20,7 +20,7 @@ struct TimingPool {
 
 const char* const kKernelNames[kNumKernels] = {"frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan",
                                                "token_gather", "kv_cosine", "kv_mean", "kv_gather",
-                                               "stream_copy", "stream_read"};
+                                               "kv_gather_rope", "stream_copy", "stream_read"};
 }  // namespace
 
 void timing_begin(int kernel, hipStream_t st) {
@@ -183,13 +183,16 @@ size_t sharpv_prune_kv_workspace(int B, int S, int n_vis, const sharpv_params* p
     return carve_kv_workspace(nullptr, B, S, n_vis).bytes;
 }
 
-int sharpv_prune_kv(const void* hidden, const void* orig, const void* K, const void* V, int64_t kv_stride_h,
-                    int64_t kv_stride_s, const int32_t* seq_offsets, const int32_t* vis_start,
-                    const int32_t* vis_offsets, int B, int S, int vis_start0, int n_vis, int d, int H, int D,
-                    int layer, const sharpv_params* params, int32_t* out_idx, int32_t* out_count, void* K_out,
-                    void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos, void* workspace,
-                    size_t workspace_bytes, void* stream) {
-    (void)layer;
+}  // extern "C"
+
+// Shared body of sharpv_prune_kv and sharpv_prune_kv_rope (rope_cos == nullptr: plain gather).
+static int prune_kv_checked(const void* hidden, const void* orig, const void* K, const void* V, int64_t kv_stride_h,
+                            int64_t kv_stride_s, const int32_t* seq_offsets, const int32_t* vis_start,
+                            const int32_t* vis_offsets, int B, int S, int vis_start0, int n_vis, int d, int H, int D,
+                            const sharpv_params* params, int32_t* out_idx, int32_t* out_count, void* K_out,
+                            void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos,
+                            const float* rope_cos, const float* rope_sin, int rope_len, int rope_layout,
+                            void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_params(params);
     if (rc != SHARPV_OK) return rc;
     if (hidden == nullptr || orig == nullptr || K == nullptr || V == nullptr || K_out == nullptr ||
@@ -225,8 +228,45 @@ int sharpv_prune_kv(const void* hidden, const void* orig, const void* K, const v
     a.dtype = params->dtype; a.kv_mode = params->kv_mode; a.M = params->M;
     a.out_idx = out_idx; a.out_count = out_count; a.K_out = K_out; a.V_out = V_out;
     a.out_cos = out_cos; a.out_mean_cos = out_mean_cos;
+    a.rope_cos = rope_cos; a.rope_sin = rope_sin; a.rope_len = rope_len; a.rope_layout = rope_layout;
     a.workspace = workspace; a.stream = (hipStream_t)stream;
     return launch_prune_kv(a);
+}
+
+extern "C" {
+
+int sharpv_prune_kv(const void* hidden, const void* orig, const void* K, const void* V, int64_t kv_stride_h,
+                    int64_t kv_stride_s, const int32_t* seq_offsets, const int32_t* vis_start,
+                    const int32_t* vis_offsets, int B, int S, int vis_start0, int n_vis, int d, int H, int D,
+                    int layer, const sharpv_params* params, int32_t* out_idx, int32_t* out_count, void* K_out,
+                    void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    (void)layer;
+    return prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, vis_start, vis_offsets, B, S,
+                            vis_start0, n_vis, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h,
+                            out_cos, out_mean_cos, nullptr, nullptr, 0, 0, workspace, workspace_bytes, stream);
+}
+
+int sharpv_prune_kv_rope(const void* hidden, const void* orig, const void* K, const void* V, int64_t kv_stride_h,
+                         int64_t kv_stride_s, const int32_t* seq_offsets, const int32_t* vis_start,
+                         const int32_t* vis_offsets, int B, int S, int vis_start0, int n_vis, int d, int H, int D,
+                         int layer, const sharpv_params* params, int32_t* out_idx, int32_t* out_count, void* K_out,
+                         void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos,
+                         const float* rope_cos, const float* rope_sin, int rope_len, int rope_layout,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    (void)layer;
+    if (rope_cos == nullptr || rope_sin == nullptr) return SHARPV_ERR_NULL;
+    if (rope_layout != SHARPV_ROPE_HALF && rope_layout != SHARPV_ROPE_INTERLEAVED) return SHARPV_ERR_PARAM;
+    if (params != nullptr && params->struct_size == sizeof(sharpv_params)) {
+        // a half row must be whole 16-byte pieces, and the tables must reach the largest possible shift
+        const int64_t esz = params->dtype == SHARPV_F32 ? 4 : 2;
+        if (D < 2 || (D * esz) % 32 != 0 || rope_len < S) return SHARPV_ERR_SHAPE;
+    }
+    if (!aligned(rope_cos, 4) || !aligned(rope_sin, 4)) return SHARPV_ERR_SHAPE;
+    return prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, vis_start, vis_offsets, B, S,
+                            vis_start0, n_vis, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h,
+                            out_cos, out_mean_cos, rope_cos, rope_sin, rope_len, rope_layout, workspace,
+                            workspace_bytes, stream);
 }
 
 int sharpv_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {

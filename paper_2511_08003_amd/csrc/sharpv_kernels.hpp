@@ -33,6 +33,8 @@ struct KvArgs {
     int32_t* out_idx; int32_t* out_count;
     void* K_out; void* V_out;
     float* out_cos; float* out_mean_cos;
+    const float* rope_cos; const float* rope_sin;   // [rope_len][D/2] each, or nullptr: plain copy of the K rows
+    int rope_len, rope_layout;
     void* workspace;
     hipStream_t stream;
 };
@@ -106,7 +108,7 @@ inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d, int dty
 
 // ---------------------------------------------------------------------------- event timing
 enum KernelId { kFrameSlab = 0, kFrameMean, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
-                kKvCosine, kKvMean, kKvGather, kStreamCopy, kStreamRead, kNumKernels };
+                kKvCosine, kKvMean, kKvGather, kKvGatherRope, kStreamCopy, kStreamRead, kNumKernels };
 
 void timing_begin(int kernel, hipStream_t st);
 void timing_end(int kernel, hipStream_t st);

@@ -11,6 +11,8 @@
 //   kv_gather   one workgroup per mask word (16 positions): output offset = popcount of the preceding
 //               mask words, rank inside the word by popcount, then batched 16-byte copies of the kept
 //               K and V rows, plane by plane.  A last workgroup writes the per-sequence counts.
+//   kv_gather_rope  the same gather with the rotary position of every kept K row re-encoded for its
+//               new place in the compacted cache (Sec. 4.1, Implementation Details).
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
@@ -294,6 +296,186 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------- gather with rotary re-encoding
+// 16-byte piece <-> floats.  bf16 -> float32 is exact; float32 -> bf16 rounds to nearest, ties to even
+// (finite values).
+template <typename T> struct Piece;
+template <> struct Piece<bf16_t> {
+    static constexpr int kElems = 8;
+    static __device__ __forceinline__ void widen(const uint4& q, float (&v)[8]) {
+        v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+        v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+        v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+        v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ uint32_t round1(float f) {
+        const uint32_t u = __float_as_uint(f);
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    static __device__ __forceinline__ uint4 narrow(const float (&v)[8]) {
+        return make_uint4(round1(v[0]) | (round1(v[1]) << 16), round1(v[2]) | (round1(v[3]) << 16),
+                          round1(v[4]) | (round1(v[5]) << 16), round1(v[6]) | (round1(v[7]) << 16));
+    }
+};
+template <> struct Piece<float> {
+    static constexpr int kElems = 4;
+    static __device__ __forceinline__ void widen(const uint4& q, float (&v)[4]) {
+        v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y); v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
+    }
+    static __device__ __forceinline__ uint4 narrow(const float (&v)[4]) {
+        return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+    }
+};
+
+// Pair (x, y) turned back by the angle whose cosine / sine are c / s (Sec. 4.1, Implementation Details:
+// the positional embedding is re-encoded for the row's new place); the two products are rounded on
+// their own, then one fused multiply-add each.
+__device__ __forceinline__ void rotate_back(float x, float y, float c, float s, float* xn, float* yn) {
+    const float ys = y * s;
+    const float xs = x * s;
+    *xn = __builtin_fmaf(x, c, ys);
+    *yn = __builtin_fmaf(y, c, -xs);
+}
+
+// kv_gather with the rotary embedding of every kept K row re-encoded on the way: a row that sat at
+// position p of its sequence and becomes that sequence's j-th kept row is turned back by delta = p - j
+// steps, with cos / sin of delta * theta_i read from the caller's tables [rope_len][D/2].
+// LAYOUT 0 pairs element i with i + D/2, LAYOUT 1 pairs 2i with 2i+1.  A thread owns the 16-byte pieces
+// q and q + pieces/2 of a kept row (for LAYOUT 0 they hold the two halves of the same pairs) in every
+// head plane; V rows are copied unchanged.  Everything else (output offset from the popcounts of the
+// preceding mask words, rank inside the word, batched loads, extra workgroup for the counts) is as in
+// kv_gather_kernel.
+template <typename T, int LAYOUT, int CH>
+__global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
+    const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
+    char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H_any,
+    const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S, int32_t* __restrict__ out_idx,
+    int32_t* __restrict__ out_count, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
+    __shared__ int scratch[kGatherThreads / 64];
+    constexpr int E = Piece<T>::kElems;
+    const int H = CH > 0 ? CH : H_any;
+    const int word = blockIdx.x;
+    if (word == n_words) {                       // extra workgroup: kept positions per sequence
+        if (sd.seq_offsets == nullptr) {
+            const int tot = kept_before(mask16, S, scratch);
+            if (threadIdx.x == 0) out_count[0] = tot;
+        } else {
+            for (int b = 0; b < sd.B; ++b) {
+                const int lo = kept_before(mask16, sd.seq_offsets[b], scratch);
+                const int hi = kept_before(mask16, sd.seq_offsets[b + 1], scratch);
+                if (threadIdx.x == 0) out_count[b] = hi - lo;
+            }
+        }
+        return;
+    }
+    const unsigned mask = mask16[word];
+    if (mask == 0u) return;                      // nothing kept here (uniform over the workgroup)
+    const int word_pos = word * kMaskWord;
+    const int base = kept_before(mask16, word_pos, scratch);
+    // sequence of the word's first position, and how many rows were kept before that sequence starts
+    int b_first = 0, first_lo = 0, first_kept = 0;
+    if (sd.seq_offsets != nullptr) {
+        while (b_first + 1 < sd.B && sd.seq_offsets[b_first + 1] <= word_pos) ++b_first;
+        first_lo = sd.seq_offsets[b_first];
+        first_kept = kept_before(mask16, first_lo, scratch);
+    }
+    const int cnt = __popc(mask);
+    const int pieces = row_bytes / 16;
+    const int hp = pieces / 2;                   // pieces per half row
+    const int half = hp * E;                     // pairs per row = D / 2
+    const int units = cnt * hp;
+    for (int w = threadIdx.x; w < units; w += kGatherThreads) {
+        const int r = w / hp;
+        const int q = w - r * hp;
+        unsigned m = mask;                       // position of the r-th kept bit
+        for (int i = 0; i < r; ++i) m &= m - 1u;
+        const int bit = __ffs(m) - 1;
+        const int pos = word_pos + bit;
+        if (q == 0) out_idx[base + r] = pos;
+        // delta = (position inside the sequence) - (rank among the sequence's kept rows)
+        int seq_lo = first_lo, seq_kept = first_kept;
+        if (sd.seq_offsets != nullptr) {
+            int b = b_first;
+            while (b + 1 < sd.B && sd.seq_offsets[b + 1] <= pos) ++b;
+            if (b != b_first) {                  // the sequence starts inside this word
+                seq_lo = sd.seq_offsets[b];
+                seq_kept = base + __popc(mask & ((1u << (seq_lo - word_pos)) - 1u));
+            }
+        }
+        const int delta = (pos - seq_lo) - (base + r - seq_kept);
+        const float* ct = rope_cos + (size_t)delta * half;
+        const float* st = rope_sin + (size_t)delta * half;
+        // table entries of this thread's pairs: LAYOUT 0: pairs q*E .. q*E+E-1 (x in piece q, y in piece
+        // q+hp); LAYOUT 1: piece q holds pairs q*E/2 .., piece q+hp holds pairs (q+hp)*E/2 ..
+        float c[E], sn[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int i = LAYOUT == 0 ? q * E + e : (e < E / 2 ? q * (E / 2) + e : (q + hp) * (E / 2) + (e - E / 2));
+            c[e] = ct[i];
+            sn[e] = st[i];
+        }
+        const long long src_off = (long long)pos * stride_s_bytes + (long long)q * 16;
+        const long long dst_off = (long long)(base + r) * row_bytes + (long long)q * 16;
+        const long long hop = (long long)hp * 16;
+        constexpr int kHeads = CH > 0 ? (CH < 4 ? CH : 4) : 2;          // heads per batch (4 loads each)
+        for (int h0 = 0; h0 < H; h0 += kHeads) {
+            uint4 kx[kHeads], ky[kHeads], vx[kHeads], vy[kHeads];
+#pragma unroll
+            for (int k = 0; k < kHeads; ++k) {
+                int h = h0 + k;
+                if (CH == 0) h = h < H ? h : H - 1;                     // a valid head, loaded twice
+                const char* pk = K + h * stride_h_bytes + src_off;
+                const char* pv = V + h * stride_h_bytes + src_off;
+                kx[k] = load_stream(reinterpret_cast<const uint4*>(pk));
+                ky[k] = load_stream(reinterpret_cast<const uint4*>(pk + hop));
+                vx[k] = load_stream(reinterpret_cast<const uint4*>(pv));
+                vy[k] = load_stream(reinterpret_cast<const uint4*>(pv + hop));
+            }
+#pragma unroll
+            for (int k = 0; k < kHeads; ++k) {
+                const int h = h0 + k;
+                if (CH == 0 && h >= H) continue;
+                float a[E], b[E], an[E], bn[E];
+                Piece<T>::widen(kx[k], a);
+                Piece<T>::widen(ky[k], b);
+                if (LAYOUT == 0) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) rotate_back(a[e], b[e], c[e], sn[e], &an[e], &bn[e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < E / 2; ++e) {
+                        rotate_back(a[2 * e], a[2 * e + 1], c[e], sn[e], &an[2 * e], &an[2 * e + 1]);
+                        rotate_back(b[2 * e], b[2 * e + 1], c[E / 2 + e], sn[E / 2 + e], &bn[2 * e], &bn[2 * e + 1]);
+                    }
+                }
+                char* ok = K_out + h * out_stride_h_bytes + dst_off;
+                char* ov = V_out + h * out_stride_h_bytes + dst_off;
+                store_stream(reinterpret_cast<uint4*>(ok), Piece<T>::narrow(an));
+                store_stream(reinterpret_cast<uint4*>(ok + hop), Piece<T>::narrow(bn));
+                store_stream(reinterpret_cast<uint4*>(ov), vx[k]);
+                store_stream(reinterpret_cast<uint4*>(ov + hop), vy[k]);
+            }
+        }
+    }
+}
+
+template <typename T, int LAYOUT>
+static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, int n_words, size_t esz) {
+#define SHARPV_GATHER_ROPE(CH_)                                                                                     \
+    hipLaunchKernelGGL((kv_gather_rope_kernel<T, LAYOUT, CH_>), dim3(n_words + 1), dim3(kGatherThreads), 0,         \
+                       a.stream, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),     \
+                       (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
+                       (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
+                       a.S, a.out_idx, a.out_count, a.rope_cos, a.rope_sin)
+    switch (a.H) {
+        case 2: SHARPV_GATHER_ROPE(2); break;
+        case 4: SHARPV_GATHER_ROPE(4); break;
+        case 8: SHARPV_GATHER_ROPE(8); break;
+        default: SHARPV_GATHER_ROPE(0);
+    }
+#undef SHARPV_GATHER_ROPE
+}
+
 // ---------------------------------------------------------------------------- host side
 int launch_prune_kv(const KvArgs& a) {
     hipStream_t st = a.stream;
@@ -327,7 +509,16 @@ int launch_prune_kv(const KvArgs& a) {
 
     const int n_words = (a.S + kMaskWord - 1) / kMaskWord;
     const uint16_t* mask16 = reinterpret_cast<const uint16_t*>(ws.group_mask);
-    {
+    if (a.rope_cos != nullptr) {
+        TimedLaunch tl(kKvGatherRope, st);
+        if (a.dtype == SHARPV_BF16) {
+            if (a.rope_layout == 0) launch_kv_gather_rope<bf16_t, 0>(a, mask16, n_words, esz);
+            else launch_kv_gather_rope<bf16_t, 1>(a, mask16, n_words, esz);
+        } else {
+            if (a.rope_layout == 0) launch_kv_gather_rope<float, 0>(a, mask16, n_words, esz);
+            else launch_kv_gather_rope<float, 1>(a, mask16, n_words, esz);
+        }
+    } else {
         TimedLaunch tl(kKvGather, st);
 #define SHARPV_GATHER(CH_)                                                                                          \
     hipLaunchKernelGGL((kv_gather_kernel<CH_>), dim3(n_words + 1), dim3(kGatherThreads), 0, st, (const char*)a.K,   \

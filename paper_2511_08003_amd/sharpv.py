@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libsharpv.so")
 F32, BF16 = 0, 1
 OK = 0
 KERNEL_NAMES = ("frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
-                "kv_cosine", "kv_mean", "kv_gather", "stream_copy", "stream_read")
+                "kv_cosine", "kv_mean", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read")
+ROPE_HALF, ROPE_INTERLEAVED = 0, 1
 
 
 class Params(C.Structure):
@@ -58,6 +59,10 @@ def load() -> C.CDLL:
     L.sharpv_prune_kv.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, ip, ip, ip, C.c_int, C.c_int, C.c_int,
                                   C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64,
                                   fp, fp, vp, C.c_size_t, vp]
+    L.sharpv_prune_kv_rope.restype = C.c_int
+    L.sharpv_prune_kv_rope.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, ip, ip, ip, C.c_int, C.c_int, C.c_int,
+                                       C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64,
+                                       fp, fp, fp, fp, C.c_int, C.c_int, vp, C.c_size_t, vp]
     L.sharpv_stream_copy.restype = C.c_int
     L.sharpv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.sharpv_stream_read.restype = C.c_int
@@ -192,7 +197,19 @@ class KvPlan:
     def run(self, hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
             vis_start0: int = 0, seq_offsets: Optional[torch.Tensor] = None,
             vis_start: Optional[torch.Tensor] = None, vis_offsets: Optional[torch.Tensor] = None,
-            layer: int = 0) -> int:
+            layer: int = 0, rope_cos: Optional[torch.Tensor] = None, rope_sin: Optional[torch.Tensor] = None,
+            rope_layout: int = ROPE_HALF) -> int:
+        """Enqueues `sharpv_prune_kv`, or `sharpv_prune_kv_rope` when the rotary tables
+        rope_cos / rope_sin ([rope_len, D/2] float32, GPU, contiguous) are given."""
+        if rope_cos is not None or rope_sin is not None:
+            return load().sharpv_prune_kv_rope(
+                hidden.data_ptr(), orig.data_ptr(), K.data_ptr(), V.data_ptr(), K.stride(0), K.stride(1),
+                _ptr(seq_offsets), _ptr(vis_start), _ptr(vis_offsets), self.B, self.S, vis_start0, self.n_vis,
+                self.d, self.H, self.D, layer, C.byref(self.params), self.out_idx.data_ptr(),
+                self.out_count.data_ptr(), self.K_out.data_ptr(), self.V_out.data_ptr(), self.K_out.stride(0),
+                _ptr(self.out_cos), _ptr(self.out_mean_cos), _ptr(rope_cos), _ptr(rope_sin),
+                0 if rope_cos is None else rope_cos.shape[0], rope_layout, self.workspace.data_ptr(),
+                self.workspace_bytes, _stream())
         return load().sharpv_prune_kv(hidden.data_ptr(), orig.data_ptr(), K.data_ptr(), V.data_ptr(),
                                       K.stride(0), K.stride(1), _ptr(seq_offsets), _ptr(vis_start),
                                       _ptr(vis_offsets), self.B, self.S, vis_start0, self.n_vis, self.d, self.H,
@@ -215,10 +232,17 @@ class KvPlan:
 def prune_kv(hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch.Tensor, vis_start0: int = 0,
              seq_offsets: Optional[torch.Tensor] = None, vis_start: Optional[torch.Tensor] = None,
              vis_offsets: Optional[torch.Tensor] = None, params: Optional[Params] = None, layer: int = 0,
-             mean_cos: bool = False, n_vis: Optional[int] = None, **over) -> Dict[str, torch.Tensor]:
+             mean_cos: bool = False, n_vis: Optional[int] = None, rope_cos: Optional[torch.Tensor] = None,
+             rope_sin: Optional[torch.Tensor] = None, rope_layout: int = ROPE_HALF,
+             **over) -> Dict[str, torch.Tensor]:
     """Intra-LLM stage for one layer: hidden [S, d], orig [n_vis, d], K / V [H, S, D] (GPU).
-    `n_vis` defaults to the number of rows of `orig`."""
-    _require_gpu(hidden, orig, seq_offsets, vis_start, vis_offsets)
+    `n_vis` defaults to the number of rows of `orig`.  With rope_cos / rope_sin ([rope_len, D/2] float32)
+    the kept K rows are re-encoded for their new positions (`sharpv_prune_kv_rope`)."""
+    _require_gpu(hidden, orig, seq_offsets, vis_start, vis_offsets, rope_cos, rope_sin)
+    for tab in (rope_cos, rope_sin):
+        if tab is not None and (tab.dtype != torch.float32 or not tab.is_contiguous() or tab.dim() != 2
+                                or tab.shape[1] * 2 != K.shape[2]):
+            raise ValueError("rotary tables must be contiguous float32 [rope_len, D/2]")
     if not (K.is_cuda and V.is_cuda) or K.stride(2) != 1 or V.stride() != K.stride():
         raise ValueError("K and V must be GPU tensors [H, S, D] with equal strides and D contiguous")
     if params is None:
@@ -228,7 +252,8 @@ def prune_kv(hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch
     B = 1 if seq_offsets is None else seq_offsets.numel() - 1
     n_vis = orig.shape[0] if n_vis is None else n_vis
     plan = KvPlan(B, S, n_vis, d, H, D, params, device=hidden.device, mean_cos=mean_cos)
-    check(plan.run(hidden, orig, K, V, vis_start0, seq_offsets, vis_start, vis_offsets, layer), "sharpv_prune_kv")
+    check(plan.run(hidden, orig, K, V, vis_start0, seq_offsets, vis_start, vis_offsets, layer, rope_cos, rope_sin,
+                   rope_layout), "sharpv_prune_kv")
     return plan.results()
 
 

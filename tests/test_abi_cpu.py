@@ -113,6 +113,24 @@ def test_prune_kv_rejects_bad_arguments_on_the_host(lib):
     assert _kv_call(lib, q) == 4
 
 
+def _kv_rope_call(lib, p, cos=0xA000, sin=0xB000, rope_len=64, layout=0, D=32, ws_bytes=1 << 30, hidden=0x1000):
+    return lib.sharpv_prune_kv_rope(hidden, 0x2000, 0x3000, 0x4000, 64 * D, D, None, None, None, 1, 64, 4, 40, 64, 2,
+                                    D, 0, C.byref(p), 0x5000, 0x6000, 0x7000, 0x8000, 64 * D, None, None, cos, sin,
+                                    rope_len, layout, 0x10000, ws_bytes, None)
+
+
+def test_prune_kv_rope_rejects_bad_arguments_on_the_host(lib):
+    p = sharpv.default_params()
+    assert _kv_rope_call(lib, p, cos=None) == 1
+    assert _kv_rope_call(lib, p, sin=None) == 1
+    assert _kv_rope_call(lib, p, layout=2) == 4
+    assert _kv_rope_call(lib, p, rope_len=63) == 2           # a shift of S-1 must have a table row
+    assert _kv_rope_call(lib, p, D=8) == 2                   # half a bf16 row of 8 elements is not whole 16-byte pieces
+    assert _kv_rope_call(lib, p, cos=0xA002) == 2            # misaligned table
+    assert _kv_rope_call(lib, p, hidden=None) == 1           # the checks of sharpv_prune_kv still apply
+    assert _kv_rope_call(lib, p, ws_bytes=8) == 5
+
+
 def test_binding_refuses_to_run_without_a_gpu():
     import torch
     if torch.cuda.is_available():

@@ -308,6 +308,87 @@ def test_error_codes_with_real_buffers():
     assert plan2.run(x) == 4
 
 
+# ----------------------------------------------------------------------------- rotary re-encoding in the K gather
+def rope_tables(rope_len, D, base=1e6):
+    """cos / sin of delta * theta_i for a rotary embedding of the given base (float32 tables, as a model caches them)."""
+    theta = base ** (-2.0 * np.arange(D // 2) / D)
+    ang = np.arange(rope_len)[:, None] * theta[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def check_kv_rope(hidden, orig, K, V, dtype, lay, layout, ragged=None, strided=False, **over):
+    H, S, D = K.shape
+    ct, st = rope_tables(S, D)
+    kw = {k: over[k] for k in ("M", "kv_mode") if k in over}
+    is_ragged = lay.B > 1 if ragged is None else ragged
+    call = dict(kw)
+    if is_ragged:
+        call.update(seq_offsets=i32(lay.seq_offsets), vis_start=i32(lay.vis_start), vis_offsets=i32(lay.vis_offsets))
+    else:
+        call.update(vis_start0=int(lay.vis_start[0]))
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    if strided:                                           # stored [S, H, D], passed as a permuted view
+        Kd = Kd.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+        Vd = Vd.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    got = sharpv.prune_kv(dev(hidden, dtype), dev(orig, dtype), Kd, Vd, n_vis=lay.n_vis,
+                          rope_cos=torch.from_numpy(ct).cuda(), rope_sin=torch.from_numpy(st).cuda(),
+                          rope_layout=layout, **call)
+    torch.cuda.synchronize()
+    exp = canon.prune_kv(hidden, orig, K, V, dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets, **kw)
+    K_exp = canon.rope_reencode(exp["K_out"], dtype, exp["idx"], lay.seq_offsets, ct, st, layout)
+    np.testing.assert_array_equal(got["counts"].cpu().numpy(), exp["counts"])
+    np.testing.assert_array_equal(got["idx"].cpu().numpy(), exp["idx"])
+    np.testing.assert_array_equal(host(got["V_out"], dtype), exp["V_out"])           # V rows are plain copies
+    np.testing.assert_array_equal(host(got["K_out"], dtype), K_exp)                  # bit for bit
+    # float64 definition: float32 arithmetic plus (bf16) one rounding to 8 significant bits
+    K_def = ref.rope_reencode(exp["K_out"], dtype, exp["idx"], lay.seq_offsets, ct, st, layout)
+    rtol = 2.0 ** -8 * 1.001 if dtype == wl.BF16 else 1e-5
+    np.testing.assert_allclose(wl.storage_to_f32(host(got["K_out"], dtype), dtype), K_def, rtol=rtol, atol=1e-5)
+    return exp, K_exp
+
+
+@pytest.mark.parametrize("nvs,tb,ta,d,H,D,dtype,layout", [
+    ([600], 9, 7, 512, 4, 128, wl.BF16, 0),        # the benchmark's cache shape (4 heads x 128), half-split pairs
+    ([600], 9, 7, 512, 4, 128, wl.BF16, 1),        # interleaved pairs
+    ([300, 5, 77], 7, 9, 264, 2, 32, wl.F32, 0),   # ragged batch, float32: sequences start inside mask words
+    ([3, 1, 2, 40, 1], 1, 2, 64, 3, 16, wl.BF16, 0),   # many short sequences in one mask word; 3 heads (any-H path)
+    ([130, 131], 0, 3, 512, 8, 64, wl.BF16, 1),
+    ([90], 2, 2, 64, 1, 16, wl.F32, 1),            # one head (any-H path), 8-byte half rows are refused below
+    ([257], 16, 16, 128, 2, 256, wl.BF16, 0),      # 512-byte rows
+])
+def test_prune_kv_rope_shapes(nvs, tb, ta, d, H, D, dtype, layout):
+    lay, hidden, orig, K, V = kv_case(900 + len(nvs) + D + layout, nvs, tb, ta, d, H, D, dtype)
+    exp, K_exp = check_kv_rope(hidden, orig, K, V, dtype, lay, layout)
+    assert 0 < len(exp["idx"]) < lay.S
+    assert not np.array_equal(K_exp, exp["K_out"])                 # rows did move
+    if lay.B == 1:
+        check_kv_rope(hidden, orig, K, V, dtype, lay, layout, ragged=True)
+        check_kv_rope(hidden, orig, K, V, dtype, lay, layout, strided=True)
+
+
+def test_prune_kv_rope_nothing_or_everything_dropped():
+    lay, hidden, orig, K, V = kv_case(921, [200], 4, 4, 256, 4, 128, wl.BF16)
+    # M below every cosine: all positions kept, every shift is zero, K leaves unchanged
+    exp, K_exp = check_kv_rope(hidden, orig, K, V, wl.BF16, lay, 0, M=-2.0)
+    assert len(exp["idx"]) == lay.S
+    np.testing.assert_array_equal(K_exp, K)
+    # M above every cosine: only the text positions remain; the trailing ones shift by the whole visual block
+    exp, K_exp = check_kv_rope(hidden, orig, K, V, wl.BF16, lay, 0, M=2.0)
+    assert len(exp["idx"]) == 8
+    np.testing.assert_array_equal(K_exp[:, :4], K[:, :4])
+    assert not np.array_equal(K_exp[:, 4:], K[:, 204:])
+    # per-sequence mean decision with re-encoding
+    lay2, h2, o2, K2, V2 = kv_case(922, [60, 70], 3, 3, 256, 2, 64, wl.BF16)
+    check_kv_rope(h2, o2, K2, V2, wl.BF16, lay2, 0, M=0.3, kv_mode=1)
+
+
+def test_prune_kv_rope_on_the_second_config(workloads):
+    cfg, tok = workloads(2)
+    lay = wl.kv_layout_for(cfg)
+    kv = wl.kv_layer_for(cfg, tok, cfg.kv_layers[0], threads=8)
+    check_kv_rope(kv["hidden"], tok.feats.reshape(-1, cfg.d), kv["K"], kv["V"], cfg.dtype, lay, 0)
+
+
 # ----------------------------------------------------------------------------- measurement aids and event timing
 @pytest.mark.parametrize("nbytes", [16, 48, 8192, 16 * 1000003, 64 << 20])
 def test_stream_copy_and_read(nbytes):

@@ -51,6 +51,9 @@ def lib() -> C.CDLL:
         L.sharpv_canon_prune_kv.restype = C.c_long
         L.sharpv_canon_prune_kv.argtypes = [vp, vp, vp, vp, C.c_int, ip, ip, ip, C.c_int, C.c_int, C.c_int, C.c_int,
                                             C.c_float, C.c_int, fp, fp, ip, ip, vp, vp]
+        L.sharpv_canon_prune_kv_mapped.restype = C.c_long
+        L.sharpv_canon_prune_kv_mapped.argtypes = [vp, vp, ip, vp, vp, C.c_int, ip, C.c_int, C.c_int, C.c_int,
+                                                   C.c_int, C.c_int, C.c_float, fp, ip, ip, ip, vp, vp]
         L.sharpv_canon_rope_reencode.restype = C.c_int
         L.sharpv_canon_rope_reencode.argtypes = [vp, C.c_int, ip, C.c_long, ip, C.c_int, C.c_int, C.c_int, fp, fp,
                                                  C.c_int, C.c_int]
@@ -179,3 +182,31 @@ def rope_reencode(K_kept: np.ndarray, dtype: int, idx: np.ndarray, seq_offsets: 
     if rc != 0:
         raise ValueError("sharpv_canon_rope_reencode: bad argument or table too short")
     return K
+
+
+def prune_kv_mapped(hidden: np.ndarray, orig: np.ndarray, orig_row: np.ndarray, Kc: np.ndarray, Vc: np.ndarray,
+                    dtype: int, seq_offsets: np.ndarray, M: float = 0.2) -> Dict[str, np.ndarray]:
+    hidden = _storage(hidden, dtype)
+    orig = _storage(orig, dtype)
+    Kc = _storage(Kc, dtype)
+    Vc = _storage(Vc, dtype)
+    so = np.ascontiguousarray(seq_offsets, np.int32)
+    rows = np.ascontiguousarray(orig_row, np.int32)
+    S_total, d = hidden.shape
+    H, _, D = Kc.shape
+    assert int(so[-1]) == S_total == len(rows)
+    B = len(so) - 1
+    cosv = np.full(S_total, np.nan, np.float32)
+    idx = np.empty(S_total, np.int32)
+    cnt = np.empty(B, np.int32)
+    rows_out = np.empty(S_total, np.int32)
+    K_out = np.empty_like(Kc)
+    V_out = np.empty_like(Vc)
+    tot = lib().sharpv_canon_prune_kv_mapped(_vp(hidden), _vp(orig), _ip(rows), _vp(Kc), _vp(Vc), dtype, _ip(so), B,
+                                             orig.shape[0], d, H, D, M, _fp(cosv), _ip(idx), _ip(cnt), _ip(rows_out),
+                                             _vp(K_out), _vp(V_out))
+    if tot < 0:
+        raise ValueError("sharpv_canon_prune_kv_mapped: bad argument")
+    return {"cos": cosv, "idx": idx[:tot].copy(), "counts": cnt, "orig_row_out": rows_out[:tot].copy(),
+            "K_out": K_out.reshape(-1)[:H * tot * D].reshape(H, tot, D).copy(),
+            "V_out": V_out.reshape(-1)[:H * tot * D].reshape(H, tot, D).copy()}

@@ -287,6 +287,69 @@ long sharpv_canon_prune_kv(const void* hidden, const void* orig, const void* Kc,
 }
 
 /* ------------------------------------------------------------------------------------------------
+ * Eq.7 on a sequence that earlier layers have already thinned out (Sec. 3.2, Degradation-Aware Pruning).
+ *
+ * hidden [S][d], K / V [H][S][D] hold the positions still alive; orig_row[s] is the row of orig
+ * [n_orig][d] behind position s, or -1 (anything outside [0, n_orig) counts as -1) for a system /
+ * instruction position, which is always kept.  A visual position is discarded iff its cosine < M.
+ * Outputs: cosv [S] (written at visual positions only); out_idx kept positions ascending; out_count [B];
+ * out_orig_row = orig_row of the kept positions; K_out, V_out [H][S_kept][D].  Returns S_kept or -1.
+ */
+long sharpv_canon_prune_kv_mapped(const void* hidden, const void* orig, const int32_t* orig_row, const void* Kc,
+                                  const void* Vc, int dtype, const int32_t* seq_offsets, int B, int n_orig, int d,
+                                  int H, int D, float M, float* cosv, int32_t* out_idx, int32_t* out_count,
+                                  int32_t* out_orig_row, void* K_out, void* V_out) {
+    if (!hidden || !orig || !orig_row || !seq_offsets || B < 1) return -1;
+    const int S = seq_offsets[B];
+    const size_t esz = dtype == CANON_F32 ? 4 : 2;
+    unsigned char* keep = (unsigned char*)malloc((size_t)S + 1);
+    memset(keep, 1, (size_t)S + 1);
+#pragma omp parallel
+    {
+        float* h = (float*)malloc((size_t)d * sizeof(float));
+        float* o = (float*)malloc((size_t)d * sizeof(float));
+#pragma omp for schedule(static)
+        for (int s = 0; s < S; ++s) {
+            const int p = orig_row[s];
+            if (p < 0 || p >= n_orig) continue;
+            widen_row(hidden, dtype, (size_t)s, d, h);
+            widen_row(orig, dtype, (size_t)p, d, o);
+            const float hh = sharpv_canon_rowdot(h, h, d);
+            const float oo = sharpv_canon_rowdot(o, o, d);
+            const float ho = sharpv_canon_rowdot(h, o, d);
+            const float c = sharpv_canon_cos(ho, hh, oo);
+            if (cosv) cosv[s] = c;
+            if (c < M) keep[s] = 0;                                                   /* Eq.7 */
+        }
+        free(h); free(o);
+    }
+    long n_kept = 0;
+    for (int b = 0; b < B; ++b) {
+        int c = 0;
+        for (int s = seq_offsets[b]; s < seq_offsets[b + 1]; ++s)
+            if (keep[s]) {
+                const int p = orig_row[s];
+                out_idx[n_kept + c] = s;
+                if (out_orig_row) out_orig_row[n_kept + c] = (p < 0 || p >= n_orig) ? -1 : p;
+                ++c;
+            }
+        out_count[b] = c;
+        n_kept += c;
+    }
+    if (Kc && Vc && K_out && V_out) {
+        for (int hh = 0; hh < H; ++hh)
+            for (long j = 0; j < n_kept; ++j) {
+                const size_t src = ((size_t)hh * S + (size_t)out_idx[j]) * D * esz;
+                const size_t dst = ((size_t)hh * n_kept + (size_t)j) * D * esz;
+                memcpy((char*)K_out + dst, (const char*)Kc + src, (size_t)D * esz);
+                memcpy((char*)V_out + dst, (const char*)Vc + src, (size_t)D * esz);
+            }
+    }
+    free(keep);
+    return n_kept;
+}
+
+/* ------------------------------------------------------------------------------------------------
  * Rotary re-encoding of the compacted K cache (Sec. 4.1, Implementation Details), in place.
  *
  * K_rows [H][n_kept][D] are the kept K rows in stream order, out_idx their packed positions.  The

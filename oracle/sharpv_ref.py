@@ -18,6 +18,9 @@ Readings taken where the paper is silent (each is listed with its reason in the 
   * top-k ties go to the lowest token index, kept tokens stay in stream order;
   * Eq.7 is applied per visual token (kv_mode 0) or to the mean over a sequence's visual
     tokens (kv_mode 1); non-visual positions are always kept; "< M" is strict;
+  * pruning carried from layer to layer (Sec. 3.2: discarded features do not propagate further)
+    is read as: a layer sees only the positions that survived the layers before it, each with
+    a pointer to the row of the original visual features it started from;
   * the positional re-encoding of Sec. 4.1 (Implementation Details) is read as: every kept K
     row gets the rotary embedding of its new place in the compacted cache; the paper names no
     rotary convention, so frequencies (as cos/sin tables) and pairing come from the caller.
@@ -186,6 +189,36 @@ def prune_kv(hidden: np.ndarray, orig: np.ndarray, Kc: np.ndarray, Vc: np.ndarra
         counts[b] = int(keep[int(seq_offsets[b]):int(seq_offsets[b + 1])].sum())
     idx = np.nonzero(keep)[0].astype(np.int32)
     return {"cos": cos, "mean_cos": mean_cos, "idx": idx, "counts": counts,
+            "K_out": np.asarray(Kc)[:, idx, :], "V_out": np.asarray(Vc)[:, idx, :]}
+
+
+def prune_kv_mapped(hidden: np.ndarray, orig: np.ndarray, orig_row: np.ndarray, Kc: np.ndarray, Vc: np.ndarray,
+                    dtype: int, seq_offsets: np.ndarray, M: float = 0.2) -> Dict[str, np.ndarray]:
+    """Eq.7 on a sequence that earlier layers have already thinned out (Sec. 3.2, Degradation-Aware
+    Pruning: a discarded token's degraded features do not propagate further, so the layers after it
+    work on the survivors only).
+
+    hidden [S, d], Kc / Vc [H, S, D] hold the positions still alive at this layer;
+    orig_row[s] is the row of `orig` that position s started from, or -1 for a system /
+    instruction position (anything outside [0, len(orig)) counts as -1).  A visual position is
+    discarded iff cos(hidden[s], orig[orig_row[s]]) < M; the others are always kept.
+    Returns cos [S] (NaN at non-visual positions), idx, counts [B], K_out, V_out and
+    orig_row_out = orig_row[idx], the map the next layer starts from."""
+    h = widen(hidden, dtype)
+    o = widen(orig, dtype)
+    rows = np.asarray(orig_row, dtype=np.int64).copy()
+    rows[(rows < 0) | (rows >= o.shape[0])] = -1
+    S_total = h.shape[0]
+    cos = np.full(S_total, np.nan)
+    keep = np.ones(S_total, dtype=bool)
+    vis = np.nonzero(rows >= 0)[0]
+    if len(vis):
+        cos[vis] = cosine(h[vis], o[rows[vis]])
+        keep[vis] = ~(cos[vis] < M)
+    so = np.asarray(seq_offsets, dtype=np.int64)
+    counts = np.array([int(keep[so[b]:so[b + 1]].sum()) for b in range(len(so) - 1)], dtype=np.int32)
+    idx = np.nonzero(keep)[0].astype(np.int32)
+    return {"cos": cos, "idx": idx, "counts": counts, "orig_row_out": rows[idx].astype(np.int32),
             "K_out": np.asarray(Kc)[:, idx, :], "V_out": np.asarray(Vc)[:, idx, :]}
 
 

@@ -330,3 +330,42 @@ def test_rope_reencode_matches_definition(layout):
     got = wl.storage_to_f32(canon.rope_reencode(Kb[:, idx], wl.BF16, idx, seq, ct, st, layout), wl.BF16)
     # one rounding to bf16 (8 significant bits: half an ulp <= 2^-8 relative) on top of the float32 arithmetic
     np.testing.assert_allclose(got, want, rtol=2.0 ** -8 * 1.001, atol=1e-6)
+
+
+# ----------------------------------------------------------------------------- pruning carried from layer to layer
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_prune_kv_mapped_matches_definition_and_block_form(dtype):
+    rng = np.random.default_rng(61 + dtype)
+    S, n_orig, d, H, D = 300, 260, 264, 2, 16
+    orig = wl.to_storage(rng.standard_normal((n_orig, d)).astype(np.float32), dtype)
+    o32 = wl.storage_to_f32(orig, dtype)
+    rows = np.full(S, -1)
+    vis = np.sort(rng.choice(S, size=200, replace=False))
+    rows[vis] = rng.choice(n_orig, size=200, replace=False)
+    h32 = rng.standard_normal((S, d)).astype(np.float32)
+    h32[vis] = o32[rows[vis]] + (rng.random((200, 1)) * 8).astype(np.float32) * h32[vis]
+    hidden = wl.to_storage(h32, dtype)
+    K = wl.to_storage(rng.standard_normal((H, S, D)).astype(np.float32), dtype)
+    V = wl.to_storage(rng.standard_normal((H, S, D)).astype(np.float32), dtype)
+    seq = np.array([0, 120, 121, 300])
+    a = ref.prune_kv_mapped(hidden, orig, rows, K, V, dtype, seq, M=0.2)
+    b = canon.prune_kv_mapped(hidden, orig, rows, K, V, dtype, seq, M=0.2)
+    np.testing.assert_allclose(b["cos"][vis], a["cos"][vis], rtol=1e-5, atol=1e-6)
+    differ = np.setxor1d(a["idx"], b["idx"])
+    assert all(abs(a["cos"][s] - 0.2) < 1e-5 for s in differ)           # only decisions on the boundary may differ
+    if len(differ) == 0:
+        for k in ("idx", "counts", "orig_row_out", "K_out", "V_out"):
+            np.testing.assert_array_equal(b[k], a[k])
+    # a contiguous block with rows in order is the single-layer form, bit for bit
+    lay = wl.make_kv_layout([100, 60], 5, 7, H, D)
+    rows2 = np.full(lay.S, -1)
+    rows2[lay.visual_positions()] = np.arange(lay.n_vis)
+    hid2 = wl.to_storage(rng.standard_normal((lay.S, d)).astype(np.float32), dtype)
+    hid2[lay.visual_positions()] = hidden[vis[:160]]
+    K2 = wl.to_storage(rng.standard_normal((H, lay.S, D)).astype(np.float32), dtype)
+    blk = canon.prune_kv(hid2, orig[rows[vis[:160]]], K2, K2, dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets)
+    mp = canon.prune_kv_mapped(hid2, orig[rows[vis[:160]]], rows2, K2, K2, dtype, lay.seq_offsets)
+    np.testing.assert_array_equal(mp["idx"], blk["idx"])
+    np.testing.assert_array_equal(mp["counts"], blk["counts"])
+    np.testing.assert_array_equal(mp["K_out"], blk["K_out"])
+    np.testing.assert_array_equal(mp["cos"][lay.visual_positions()], blk["cos"])

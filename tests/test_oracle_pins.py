@@ -447,3 +447,82 @@ def test_rope_reencode_identity_norms_batches_and_layouts():
     perm[0::2], perm[1::2] = np.arange(D // 2), np.arange(D // 2) + D // 2    # interleaved slot <- half-split slot
     inter = ref.rope_reencode(K[:, idx][:, :, perm], 0, idx, seq, ct, st, 1)
     np.testing.assert_array_equal(inter, out[:, :, perm])
+
+
+# ----------------------------------------------------------------------------- pruning carried from layer to layer
+def _mapped_case(seed, S=60, n_orig=40, d=24, H=2, D=4):
+    rng = np.random.default_rng(seed)
+    orig = rng.standard_normal((n_orig, d)).astype(np.float32)
+    rows = np.full(S, -1)
+    vis = np.sort(rng.choice(S, size=n_orig, replace=False))
+    rows[vis] = rng.permutation(n_orig)                      # tokens refer to shuffled rows of orig
+    hidden = rng.standard_normal((S, d)).astype(np.float32)
+    sig = rng.random(n_orig) * 8
+    hidden[vis] = orig[rows[vis]] + sig[:, None] * hidden[vis]
+    K = rng.standard_normal((H, S, D)).astype(np.float32)
+    V = rng.standard_normal((H, S, D)).astype(np.float32)
+    return hidden, orig, rows, vis, K, V
+
+
+def test_mapped_kv_pruning_reduces_to_the_block_form_and_to_library_cosines():
+    # a contiguous visual block with rows in order is exactly the single-layer form
+    rng = np.random.default_rng(51)
+    tb, nv, ta, d = 3, 30, 4, 16
+    S = tb + nv + ta
+    orig = rng.standard_normal((nv, d)).astype(np.float32)
+    hidden = rng.standard_normal((S, d)).astype(np.float32)
+    hidden[tb:tb + nv] = orig + rng.random((nv, 1)).astype(np.float32) * 8 * hidden[tb:tb + nv]
+    K = rng.standard_normal((2, S, 4)).astype(np.float32)
+    rows = np.full(S, -1); rows[tb:tb + nv] = np.arange(nv)
+    a = ref.prune_kv(hidden, orig, K, K, 0, np.array([0, S]), np.array([tb]), np.array([0, nv]), M=0.2)
+    b = ref.prune_kv_mapped(hidden, orig, rows, K, K, 0, np.array([0, S]), M=0.2)
+    np.testing.assert_array_equal(a["idx"], b["idx"])
+    np.testing.assert_array_equal(a["counts"], b["counts"])
+    np.testing.assert_array_equal(a["K_out"], b["K_out"])
+    np.testing.assert_allclose(b["cos"][tb:tb + nv], a["cos"], rtol=1e-12)
+    assert np.all(np.isnan(b["cos"][:tb])) and np.all(np.isnan(b["cos"][tb + nv:]))
+    # shuffled rows: the cosines are those of the rows gathered with numpy, via scipy's cosine distance
+    from scipy.spatial.distance import cosine as cosine_distance
+    hidden, orig, rows, vis, K, V = _mapped_case(52)
+    o = ref.prune_kv_mapped(hidden, orig, rows, K, V, 0, np.array([0, 25, 60]), M=0.2)
+    want = np.array([1.0 - cosine_distance(hidden[s].astype(np.float64), orig[rows[s]].astype(np.float64)) for s in vis])
+    np.testing.assert_allclose(o["cos"][vis], want, rtol=1e-10)
+    kept = np.ones(60, bool); kept[vis] = ~(want < 0.2)
+    np.testing.assert_array_equal(o["idx"], np.nonzero(kept)[0])
+    np.testing.assert_array_equal(o["counts"], [kept[:25].sum(), kept[25:].sum()])
+    np.testing.assert_array_equal(o["orig_row_out"], rows[kept])
+    np.testing.assert_array_equal(o["V_out"], V[:, kept])
+    # entries outside [0, n_orig) are non-visual positions: always kept, no cosine
+    bad = rows.copy(); bad[vis[:3]] = [40, 999, -7]
+    o2 = ref.prune_kv_mapped(hidden, orig, bad, K, V, 0, np.array([0, 60]), M=2.0)
+    np.testing.assert_array_equal(o2["idx"], np.sort(np.concatenate([np.nonzero(rows < 0)[0], vis[:3]])))
+    assert np.all(o2["orig_row_out"] == -1)
+
+
+def test_pruning_carried_over_layers_is_the_intersection_of_the_layer_masks():
+    # three layers on shrinking sequences == per-layer Eq.7 masks on the full sequence, intersected
+    rng = np.random.default_rng(53)
+    hidden0, orig, rows, vis, K, V = _mapped_case(54, S=90, n_orig=70)
+    S = 90
+    seq = np.array([0, 40, 90])
+    layers = [hidden0]
+    for l in range(2):                                                   # later layers drift further
+        h = layers[-1].copy()
+        h[vis] += rng.standard_normal((len(vis), h.shape[1])).astype(np.float32) * rng.random((len(vis), 1)) * 6
+        layers.append(h)
+    alive = np.arange(S)
+    cur_rows, cur_seq = rows.copy(), seq.copy()
+    want_alive = np.ones(S, bool)
+    for h_full in layers:
+        o = ref.prune_kv_mapped(h_full[alive], orig, cur_rows, K[:, alive], V[:, alive], 0, cur_seq, M=0.2)
+        c_full = np.array([ref.cosine(h_full[s].astype(np.float64)[None], orig[rows[s]].astype(np.float64)[None])[0]
+                           for s in vis])
+        m = np.ones(S, bool); m[vis] = ~(c_full < 0.2)
+        want_alive &= m
+        np.testing.assert_array_equal(alive[o["idx"]], np.nonzero(want_alive)[0])
+        np.testing.assert_array_equal(o["K_out"], K[:, want_alive])
+        alive = alive[o["idx"]]
+        cur_rows = o["orig_row_out"]
+        np.testing.assert_array_equal(cur_rows, rows[want_alive])
+        cur_seq = np.concatenate([[0], np.cumsum(o["counts"])])
+    assert 0 < want_alive.sum() < S

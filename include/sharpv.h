@@ -169,6 +169,39 @@ int sharpv_prune_kv_rope(
     void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Intra-LLM stage carried from layer to layer (Sec. 3.2, Degradation-Aware Pruning: what a layer
+ * discards does not propagate further, so the layers after it work on the survivors only).
+ *
+ * hidden [S, d] and K / V [H, S, D] hold the positions still alive at this layer; orig_row[s] is the row
+ * of orig [n_orig, d] that position s started from, or -1 for a system / instruction position (any value
+ * outside [0, n_orig) counts as -1).  A visual position is discarded iff the cosine between its hidden
+ * state and that row is below M (Eq.7, per token: params->kv_mode must be 0); the others are always kept.
+ * Beside the outputs of sharpv_prune_kv it writes out_orig_row[j] = orig_row[out_idx[j]], which is the
+ * orig_row of the next layer's (shorter) sequence; out_cos, if given, is indexed by POSITION ([S], written
+ * at visual positions only).  With rope_cos / rope_sin non-NULL the kept K rows are re-encoded exactly as
+ * by sharpv_prune_kv_rope (positions counted inside the current, already shortened sequences).
+ * seq_offsets may be NULL when B == 1.  Workspace: sharpv_prune_kv_carried_workspace(B, S, params).
+ */
+size_t sharpv_prune_kv_carried_workspace(int B, int S, const sharpv_params* params /* host */);
+
+int sharpv_prune_kv_carried(
+    const void* hidden,            /* device [S, d] */
+    const void* orig,              /* device [n_orig, d] */
+    const int32_t* orig_row,       /* device [S] */
+    const void* K, const void* V,  /* device [H, S, D] (strided) */
+    int64_t kv_stride_h, int64_t kv_stride_s,
+    const int32_t* seq_offsets,    /* device [B+1] or NULL (B == 1) */
+    int B, int S, int n_orig, int d, int H, int D, int layer,
+    const sharpv_params* params,   /* host */
+    int32_t* out_idx, int32_t* out_count,
+    void* K_out, void* V_out, int64_t out_stride_h,
+    int32_t* out_orig_row,         /* device, capacity S */
+    float* out_cos,                /* device [S] or NULL */
+    const float* rope_cos, const float* rope_sin, int rope_len, int rope_layout,   /* both NULL: K rows copied as they are */
+    void* workspace, size_t workspace_bytes,
+    void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the launch stream (for benchmarks; off by default).
  * While enabled, every kernel launch of the two entry points is bracketed by a pair of events
  * taken from a pool of `max_launches` pairs (launches beyond the pool go untimed).

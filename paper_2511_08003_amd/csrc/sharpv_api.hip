@@ -192,19 +192,24 @@ static int prune_kv_checked(const void* hidden, const void* orig, const void* K,
                             const sharpv_params* params, int32_t* out_idx, int32_t* out_count, void* K_out,
                             void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos,
                             const float* rope_cos, const float* rope_sin, int rope_len, int rope_layout,
+                            const int32_t* orig_row, int32_t* out_orig_row,
                             void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_params(params);
     if (rc != SHARPV_OK) return rc;
     if (hidden == nullptr || orig == nullptr || K == nullptr || V == nullptr || K_out == nullptr ||
         V_out == nullptr || out_idx == nullptr || out_count == nullptr)
         return SHARPV_ERR_NULL;
-    rc = check_kv_shape(B, S, n_vis, d);
+    rc = check_kv_shape(B, S, orig_row != nullptr ? 0 : n_vis, d);
     if (rc != SHARPV_OK) return rc;
-    const bool ragged = seq_offsets != nullptr || vis_start != nullptr || vis_offsets != nullptr;
-    if (ragged && (seq_offsets == nullptr || vis_start == nullptr || vis_offsets == nullptr)) return SHARPV_ERR_NULL;
-    if (!ragged) {
-        if (B != 1) return SHARPV_ERR_NULL;
-        if (vis_start0 < 0 || (long long)vis_start0 + n_vis > S) return SHARPV_ERR_SHAPE;
+    if (orig_row != nullptr) {                   // map form: only seq_offsets describes the batch
+        if (B > 1 && seq_offsets == nullptr) return SHARPV_ERR_NULL;
+    } else {
+        const bool ragged = seq_offsets != nullptr || vis_start != nullptr || vis_offsets != nullptr;
+        if (ragged && (seq_offsets == nullptr || vis_start == nullptr || vis_offsets == nullptr)) return SHARPV_ERR_NULL;
+        if (!ragged) {
+            if (B != 1) return SHARPV_ERR_NULL;
+            if (vis_start0 < 0 || (long long)vis_start0 + n_vis > S) return SHARPV_ERR_SHAPE;
+        }
     }
     const int64_t esz = params->dtype == SHARPV_F32 ? 4 : 2;
     if (H < 1 || D < 1 || (D * esz) % 16 != 0) return SHARPV_ERR_SHAPE;
@@ -216,14 +221,15 @@ static int prune_kv_checked(const void* hidden, const void* orig, const void* K,
         return SHARPV_ERR_SHAPE;
     if (K_out == K || V_out == V || K_out == V || V_out == K) return SHARPV_ERR_SHAPE;
     if (workspace == nullptr || !aligned(workspace, 256) ||
-        workspace_bytes < carve_kv_workspace(nullptr, B, S, n_vis).bytes)
+        workspace_bytes < carve_kv_workspace(nullptr, B, S, orig_row != nullptr ? S : n_vis).bytes)
         return SHARPV_ERR_WORKSPACE;
 
     KvArgs a;
     a.hidden = hidden; a.orig = orig; a.K = K; a.V = V;
     a.kv_stride_h = kv_stride_h; a.kv_stride_s = kv_stride_s; a.out_stride_h = out_stride_h;
     a.sd.seq_offsets = seq_offsets; a.sd.vis_start = vis_start; a.sd.vis_offsets = vis_offsets;
-    a.sd.B = B; a.sd.vis_start0 = vis_start0; a.sd.n_vis = n_vis;
+    a.sd.B = B; a.sd.vis_start0 = vis_start0; a.sd.n_vis = n_vis; a.sd.orig_row = orig_row;
+    a.out_orig_row = out_orig_row;
     a.B = B; a.S = S; a.n_vis = n_vis; a.d = d; a.H = H; a.D = D;
     a.dtype = params->dtype; a.kv_mode = params->kv_mode; a.M = params->M;
     a.out_idx = out_idx; a.out_count = out_count; a.K_out = K_out; a.V_out = V_out;
@@ -244,7 +250,8 @@ int sharpv_prune_kv(const void* hidden, const void* orig, const void* K, const v
     (void)layer;
     return prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, vis_start, vis_offsets, B, S,
                             vis_start0, n_vis, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h,
-                            out_cos, out_mean_cos, nullptr, nullptr, 0, 0, workspace, workspace_bytes, stream);
+                            out_cos, out_mean_cos, nullptr, nullptr, 0, 0, nullptr, nullptr, workspace, workspace_bytes,
+                            stream);
 }
 
 int sharpv_prune_kv_rope(const void* hidden, const void* orig, const void* K, const void* V, int64_t kv_stride_h,
@@ -265,7 +272,42 @@ int sharpv_prune_kv_rope(const void* hidden, const void* orig, const void* K, co
     if (!aligned(rope_cos, 4) || !aligned(rope_sin, 4)) return SHARPV_ERR_SHAPE;
     return prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, vis_start, vis_offsets, B, S,
                             vis_start0, n_vis, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h,
-                            out_cos, out_mean_cos, rope_cos, rope_sin, rope_len, rope_layout, workspace,
+                            out_cos, out_mean_cos, rope_cos, rope_sin, rope_len, rope_layout, nullptr, nullptr,
+                            workspace, workspace_bytes, stream);
+}
+
+size_t sharpv_prune_kv_carried_workspace(int B, int S, const sharpv_params* params) {
+    return sharpv_prune_kv_workspace(B, S, S, params);
+}
+
+int sharpv_prune_kv_carried(const void* hidden, const void* orig, const int32_t* orig_row, const void* K, const void* V,
+                            int64_t kv_stride_h, int64_t kv_stride_s, const int32_t* seq_offsets, int B, int S,
+                            int n_orig, int d, int H, int D, int layer, const sharpv_params* params,
+                            int32_t* out_idx, int32_t* out_count, void* K_out, void* V_out, int64_t out_stride_h,
+                            int32_t* out_orig_row, float* out_cos, const float* rope_cos, const float* rope_sin,
+                            int rope_len, int rope_layout, void* workspace, size_t workspace_bytes, void* stream) {
+    (void)layer;
+    if (orig_row == nullptr || out_orig_row == nullptr) return SHARPV_ERR_NULL;
+    if (n_orig < 1) return SHARPV_ERR_SHAPE;
+    if (params != nullptr && params->struct_size == sizeof(sharpv_params) && params->kv_mode != 0)
+        return SHARPV_ERR_PARAM;                 // the per-sequence mean decision has no use for a map
+    if (!aligned(orig_row, 4) || !aligned(out_orig_row, 4)) return SHARPV_ERR_SHAPE;
+    const bool rope = rope_cos != nullptr || rope_sin != nullptr;
+    if (rope) {
+        if (rope_cos == nullptr || rope_sin == nullptr) return SHARPV_ERR_NULL;
+        if (rope_layout != SHARPV_ROPE_HALF && rope_layout != SHARPV_ROPE_INTERLEAVED) return SHARPV_ERR_PARAM;
+        if (params != nullptr && params->struct_size == sizeof(sharpv_params)) {
+            const int64_t esz = params->dtype == SHARPV_F32 ? 4 : 2;
+            if (D < 2 || (D * esz) % 32 != 0 || rope_len < S) return SHARPV_ERR_SHAPE;
+        }
+        if (!aligned(rope_cos, 4) || !aligned(rope_sin, 4)) return SHARPV_ERR_SHAPE;
+    }
+    // the shape checks take the number of rows of orig where the block form takes n_vis <= S; here a
+    // shrunken sequence may well be shorter than orig, so S is checked on its own and n_orig rides along
+    if (S < 1) return SHARPV_ERR_SHAPE;
+    return prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, nullptr, nullptr, B, S, 0,
+                            n_orig, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h, out_cos, nullptr,
+                            rope_cos, rope_sin, rope_len, rope_layout, orig_row, out_orig_row, workspace,
                             workspace_bytes, stream);
 }
 

@@ -21,7 +21,9 @@ struct SeqDesc {
     const int32_t* vis_offsets;     // [B+1]
     int B;
     int vis_start0;
-    int n_vis;
+    int n_vis;                      // rows of orig
+    const int32_t* orig_row;        // [S] position -> row of orig (< 0 or >= n_vis: not a visual token), or nullptr:
+                                    // then the visual tokens are the contiguous blocks described above
 };
 
 struct KvArgs {
@@ -33,6 +35,7 @@ struct KvArgs {
     int32_t* out_idx; int32_t* out_count;
     void* K_out; void* V_out;
     float* out_cos; float* out_mean_cos;
+    int32_t* out_orig_row;                          // orig_row of the kept positions (map form only), or nullptr
     const float* rope_cos; const float* rope_sin;   // [rope_len][D/2] each, or nullptr: plain copy of the K rows
     int rope_len, rope_layout;
     void* workspace;

@@ -19,6 +19,12 @@ namespace sharpv {
 
 // Where packed position s sits: returns true and the row of `orig` when s is a visual token.
 __device__ __forceinline__ bool locate_visual(const SeqDesc& sd, int s, int* orig_row, int* seq) {
+    if (sd.orig_row != nullptr) {                // explicit map (sequence already thinned out by earlier layers)
+        const int p = sd.orig_row[s];
+        *orig_row = p;
+        *seq = 0;
+        return p >= 0 && p < sd.n_vis;
+    }
     if (sd.seq_offsets == nullptr) {
         const int rel = s - sd.vis_start0;
         *orig_row = rel;
@@ -126,7 +132,8 @@ __global__ __launch_bounds__(kCosRows * 64) void kv_cosine_kernel(const T* __res
             if constexpr (NS > 0) c = row_cosine<T, NS, FULL>(hrow, orow, nchunks, lane);
             else c = row_cosine_loop<T>(hrow, orow, nchunks, lane);
             keep = !(c < M);                            // Eq.7: discard iff cos < M
-            if (lane == 0 && cos_out != nullptr) cos_out[p] = c;
+            // by visual token, or by position when the visual tokens are given by a map
+            if (lane == 0 && cos_out != nullptr) cos_out[sd.orig_row != nullptr ? s : p] = c;
         }
     }
     if (lane == 0) keep_flag[wave] = keep;
@@ -240,7 +247,7 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
     char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H_any,
     const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S, int32_t* __restrict__ out_idx,
-    int32_t* __restrict__ out_count) {
+    int32_t* __restrict__ out_count, int32_t* __restrict__ out_orig_row) {
     __shared__ int scratch[kGatherThreads / 64];
     const int H = CH > 0 ? CH : H_any;
     const int word = blockIdx.x;
@@ -271,7 +278,13 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
         unsigned m = mask;                       // position of the r-th kept bit
         for (int i = 0; i < r; ++i) m &= m - 1u;
         const int pos = word * kMaskWord + (__ffs(m) - 1);
-        if (q == 0) out_idx[base + r] = pos;
+        if (q == 0) {
+            out_idx[base + r] = pos;
+            if (out_orig_row != nullptr) {       // the next layer's map: the row behind each kept position
+                const int p = sd.orig_row[pos];
+                out_orig_row[base + r] = (p >= 0 && p < sd.n_vis) ? p : -1;
+            }
+        }
         if (K == nullptr) continue;
         const long long src_off = (long long)pos * stride_s_bytes + (long long)q * 16;
         const long long dst_off = (long long)(base + r) * row_bytes + (long long)q * 16;
@@ -350,7 +363,8 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
     char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H_any,
     const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S, int32_t* __restrict__ out_idx,
-    int32_t* __restrict__ out_count, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
+    int32_t* __restrict__ out_count, int32_t* __restrict__ out_orig_row, const float* __restrict__ rope_cos,
+    const float* __restrict__ rope_sin) {
     __shared__ int scratch[kGatherThreads / 64];
     constexpr int E = Piece<T>::kElems;
     const int H = CH > 0 ? CH : H_any;
@@ -391,7 +405,13 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
         for (int i = 0; i < r; ++i) m &= m - 1u;
         const int bit = __ffs(m) - 1;
         const int pos = word_pos + bit;
-        if (q == 0) out_idx[base + r] = pos;
+        if (q == 0) {
+            out_idx[base + r] = pos;
+            if (out_orig_row != nullptr) {       // the next layer's map: the row behind each kept position
+                const int p = sd.orig_row[pos];
+                out_orig_row[base + r] = (p >= 0 && p < sd.n_vis) ? p : -1;
+            }
+        }
         // delta = (position inside the sequence) - (rank among the sequence's kept rows)
         int seq_lo = first_lo, seq_kept = first_kept;
         if (sd.seq_offsets != nullptr) {
@@ -466,7 +486,7 @@ static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, int n
                        a.stream, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),     \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
                        (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
-                       a.S, a.out_idx, a.out_count, a.rope_cos, a.rope_sin)
+                       a.S, a.out_idx, a.out_count, a.out_orig_row, a.rope_cos, a.rope_sin)
     switch (a.H) {
         case 2: SHARPV_GATHER_ROPE(2); break;
         case 4: SHARPV_GATHER_ROPE(4); break;
@@ -480,7 +500,7 @@ static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, int n
 int launch_prune_kv(const KvArgs& a) {
     hipStream_t st = a.stream;
     const int n_groups = (a.S + kGroup - 1) / kGroup;
-    KvWorkspace ws = carve_kv_workspace(a.workspace, a.B, a.S, a.n_vis);
+    KvWorkspace ws = carve_kv_workspace(a.workspace, a.B, a.S, a.sd.orig_row != nullptr ? a.S : a.n_vis);
     float* cos_buf = a.out_cos != nullptr ? a.out_cos : ws.cosv;
     const bool need_mean = a.kv_mode == 1 || a.out_mean_cos != nullptr;
     float* cos_dst = (need_mean || a.out_cos != nullptr) ? cos_buf : nullptr;
@@ -525,7 +545,7 @@ int launch_prune_kv(const KvArgs& a) {
                        (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),                                  \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
                        (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
-                       a.S, a.out_idx, a.out_count)
+                       a.S, a.out_idx, a.out_count, a.out_orig_row)
         switch (a.H) {
             case 1: SHARPV_GATHER(1); break;
             case 2: SHARPV_GATHER(2); break;

@@ -63,6 +63,12 @@ def load() -> C.CDLL:
     L.sharpv_prune_kv_rope.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, ip, ip, ip, C.c_int, C.c_int, C.c_int,
                                        C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64,
                                        fp, fp, fp, fp, C.c_int, C.c_int, vp, C.c_size_t, vp]
+    L.sharpv_prune_kv_carried_workspace.restype = C.c_size_t
+    L.sharpv_prune_kv_carried_workspace.argtypes = [C.c_int, C.c_int, pp]
+    L.sharpv_prune_kv_carried.restype = C.c_int
+    L.sharpv_prune_kv_carried.argtypes = [vp, vp, ip, vp, vp, C.c_int64, C.c_int64, ip, C.c_int, C.c_int, C.c_int,
+                                          C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64, ip, fp,
+                                          fp, fp, C.c_int, C.c_int, vp, C.c_size_t, vp]
     L.sharpv_stream_copy.restype = C.c_int
     L.sharpv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.sharpv_stream_read.restype = C.c_int
@@ -255,6 +261,48 @@ def prune_kv(hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch
     check(plan.run(hidden, orig, K, V, vis_start0, seq_offsets, vis_start, vis_offsets, layer, rope_cos, rope_sin,
                    rope_layout), "sharpv_prune_kv")
     return plan.results()
+
+
+def prune_kv_carried(hidden: torch.Tensor, orig: torch.Tensor, orig_row: torch.Tensor, K: torch.Tensor,
+                     V: torch.Tensor, seq_offsets: Optional[torch.Tensor] = None, params: Optional[Params] = None,
+                     layer: int = 0, rope_cos: Optional[torch.Tensor] = None, rope_sin: Optional[torch.Tensor] = None,
+                     rope_layout: int = ROPE_HALF, **over) -> Dict[str, torch.Tensor]:
+    """Intra-LLM stage on a sequence already thinned out by earlier layers (`sharpv_prune_kv_carried`):
+    hidden [S, d], K / V [H, S, D] of the positions still alive, orig [n_orig, d], orig_row [S] int32
+    (row of orig behind each position, -1 for non-visual positions).  Returns idx, counts, K_out, V_out,
+    cos (by position) and orig_row_out, the map for the next layer."""
+    _require_gpu(hidden, orig, orig_row, seq_offsets, rope_cos, rope_sin)
+    if not (K.is_cuda and V.is_cuda) or K.stride(2) != 1 or V.stride() != K.stride():
+        raise ValueError("K and V must be GPU tensors [H, S, D] with equal strides and D contiguous")
+    if orig_row.dtype != torch.int32 or orig_row.numel() != hidden.shape[0]:
+        raise ValueError("orig_row must be int32 [S]")
+    if params is None:
+        params = default_params(dtype_of(hidden), **over)
+    L = load()
+    S, d = hidden.shape
+    H, _, D = K.shape
+    B = 1 if seq_offsets is None else seq_offsets.numel() - 1
+    dev = hidden.device
+    nbytes = L.sharpv_prune_kv_carried_workspace(B, S, C.byref(params))
+    if nbytes == 0:
+        raise ValueError("sharpv_prune_kv_carried_workspace rejected the shape or the parameters")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    out_idx = torch.empty(S, dtype=torch.int32, device=dev)
+    out_count = torch.empty(B, dtype=torch.int32, device=dev)
+    out_rows = torch.empty(S, dtype=torch.int32, device=dev)
+    K_out = torch.empty((H, S, D), dtype=K.dtype, device=dev)
+    V_out = torch.empty((H, S, D), dtype=K.dtype, device=dev)
+    out_cos = torch.full((S,), float("nan"), dtype=torch.float32, device=dev)
+    check(L.sharpv_prune_kv_carried(hidden.data_ptr(), orig.data_ptr(), orig_row.data_ptr(), K.data_ptr(),
+                                    V.data_ptr(), K.stride(0), K.stride(1), _ptr(seq_offsets), B, S, orig.shape[0], d,
+                                    H, D, layer, C.byref(params), out_idx.data_ptr(), out_count.data_ptr(),
+                                    K_out.data_ptr(), V_out.data_ptr(), K_out.stride(0), out_rows.data_ptr(),
+                                    out_cos.data_ptr(), _ptr(rope_cos), _ptr(rope_sin),
+                                    0 if rope_cos is None else rope_cos.shape[0], rope_layout, ws.data_ptr(), nbytes,
+                                    _stream()), "sharpv_prune_kv_carried")
+    total = int(out_count.sum().item())
+    return {"idx": out_idx[:total], "counts": out_count, "orig_row_out": out_rows[:total], "cos": out_cos,
+            "K_out": K_out[:, :total, :], "V_out": V_out[:, :total, :]}
 
 
 # ----------------------------------------------------------------------------- measurement aids

@@ -131,6 +131,28 @@ def test_prune_kv_rope_rejects_bad_arguments_on_the_host(lib):
     assert _kv_rope_call(lib, p, ws_bytes=8) == 5
 
 
+def _kv_carried_call(lib, p, rows=0x9000, out_rows=0xC000, n_orig=500, B=1, so=None, cos=None, sin=None,
+                     rope_len=0, S=64, ws_bytes=1 << 30):
+    return lib.sharpv_prune_kv_carried(0x1000, 0x2000, rows, 0x3000, 0x4000, 64 * 32, 32, so, B, S, n_orig, 64, 2, 32,
+                                       0, C.byref(p), 0x5000, 0x6000, 0x7000, 0x8000, 64 * 32, out_rows, None, cos,
+                                       sin, rope_len, 0, 0x10000, ws_bytes, None)
+
+
+def test_prune_kv_carried_rejects_bad_arguments_on_the_host(lib):
+    p = sharpv.default_params()
+    assert lib.sharpv_prune_kv_carried_workspace(1, 64, C.byref(p)) == lib.sharpv_prune_kv_workspace(1, 64, 64, C.byref(p))
+    assert _kv_carried_call(lib, p, rows=None) == 1
+    assert _kv_carried_call(lib, p, out_rows=None) == 1
+    assert _kv_carried_call(lib, p, n_orig=0) == 2
+    assert _kv_carried_call(lib, p, B=2) == 1                # a batch needs seq_offsets
+    assert _kv_carried_call(lib, p, cos=0xA000) == 1         # one rotary table without the other
+    assert _kv_carried_call(lib, p, cos=0xA000, sin=0xB000, rope_len=10) == 2
+    assert _kv_carried_call(lib, p, rows=0x9001) == 2
+    assert _kv_carried_call(lib, p, ws_bytes=8) == 5
+    q = sharpv.default_params(); q.kv_mode = 1
+    assert _kv_carried_call(lib, q) == 4                     # per-token decisions only
+
+
 def test_binding_refuses_to_run_without_a_gpu():
     import torch
     if torch.cuda.is_available():

@@ -389,6 +389,107 @@ def test_prune_kv_rope_on_the_second_config(workloads):
     check_kv_rope(kv["hidden"], tok.feats.reshape(-1, cfg.d), kv["K"], kv["V"], cfg.dtype, lay, 0)
 
 
+# ----------------------------------------------------------------------------- pruning carried from layer to layer
+def carried_case(seed, seq_lens, n_orig, d, H, D, dtype, vis_frac=0.8):
+    """A packed batch whose visual positions are scattered (as after earlier pruning) and point to
+    shuffled rows of orig."""
+    rng = np.random.default_rng(seed)
+    S = int(sum(seq_lens))
+    seq = np.concatenate([[0], np.cumsum(seq_lens)]).astype(np.int32)
+    n_vis = min(n_orig, int(S * vis_frac))
+    rows = np.full(S, -1, np.int32)
+    vis = np.sort(rng.choice(S, size=n_vis, replace=False))
+    rows[vis] = rng.choice(n_orig, size=n_vis, replace=False)
+    orig = wl.to_storage(rng.standard_normal((n_orig, d)).astype(np.float32), dtype)
+    o32 = wl.storage_to_f32(orig, dtype)
+    h32 = rng.standard_normal((S, d)).astype(np.float32)
+    h32[vis] = o32[rows[vis]] + (rng.random((n_vis, 1)) * 8).astype(np.float32) * h32[vis]
+    hidden = wl.to_storage(h32, dtype)
+    K = wl.to_storage(rng.standard_normal((H, S, D)).astype(np.float32), dtype)
+    V = wl.to_storage(rng.standard_normal((H, S, D)).astype(np.float32), dtype)
+    return seq, rows, vis, hidden, orig, K, V
+
+
+def check_kv_carried(seq, rows, hidden, orig, K, V, dtype, M=0.2, rope_layout=None):
+    S = hidden.shape[0]
+    kw = {}
+    if rope_layout is not None:
+        ct, st = rope_tables(S, K.shape[2])
+        kw = dict(rope_cos=torch.from_numpy(ct).cuda(), rope_sin=torch.from_numpy(st).cuda(), rope_layout=rope_layout)
+    so = i32(seq) if len(seq) > 2 else None
+    got = sharpv.prune_kv_carried(dev(hidden, dtype), dev(orig, dtype), i32(rows), dev(K, dtype), dev(V, dtype),
+                                  seq_offsets=so, M=M, **kw)
+    torch.cuda.synchronize()
+    exp = canon.prune_kv_mapped(hidden, orig, rows, K, V, dtype, seq, M=M)
+    np.testing.assert_array_equal(got["counts"].cpu().numpy(), exp["counts"])
+    np.testing.assert_array_equal(got["idx"].cpu().numpy(), exp["idx"])
+    np.testing.assert_array_equal(got["orig_row_out"].cpu().numpy(), exp["orig_row_out"])
+    np.testing.assert_array_equal(got["cos"].cpu().numpy(), exp["cos"])              # NaN where nothing is written
+    K_exp = exp["K_out"]
+    if rope_layout is not None:
+        K_exp = canon.rope_reencode(K_exp, dtype, exp["idx"], seq, ct, st, rope_layout)
+    np.testing.assert_array_equal(host(got["K_out"], dtype), K_exp)
+    np.testing.assert_array_equal(host(got["V_out"], dtype), exp["V_out"])
+    a = ref.prune_kv_mapped(hidden, orig, rows, K, V, dtype, seq, M=M)
+    vis = (rows >= 0) & (rows < orig.shape[0])
+    np.testing.assert_allclose(got["cos"].cpu().numpy()[vis], a["cos"][vis], rtol=RTOL, atol=ATOL)
+    return exp
+
+
+@pytest.mark.parametrize("seq_lens,n_orig,d,H,D,dtype", [
+    ([700], 900, 512, 4, 128, wl.BF16),              # more rows in orig than positions left
+    ([300, 1, 77, 200], 400, 264, 2, 32, wl.F32),    # ragged batch, a one-position sequence
+    ([45], 30, 64, 3, 16, wl.BF16),
+    ([1000, 1000], 1500, 3584, 4, 128, wl.BF16),     # model width of the benchmark
+])
+def test_prune_kv_carried_shapes(seq_lens, n_orig, d, H, D, dtype):
+    seq, rows, vis, hidden, orig, K, V = carried_case(940 + len(seq_lens) + D, seq_lens, n_orig, d, H, D, dtype)
+    exp = check_kv_carried(seq, rows, hidden, orig, K, V, dtype)
+    assert 0 < len(exp["idx"]) < hidden.shape[0]
+    check_kv_carried(seq, rows, hidden, orig, K, V, dtype, rope_layout=0)
+    bad = rows.copy()
+    bad[vis[:4]] = [n_orig, n_orig + 7, -3, 2**30]           # out-of-range rows count as non-visual positions
+    check_kv_carried(seq, bad, hidden, orig, K, V, dtype, M=2.0)
+
+
+def test_prune_kv_carried_block_map_equals_plain_call():
+    lay, hidden, orig, K, V = kv_case(950, [300, 120], 6, 10, 768, 4, 64, wl.BF16)
+    rows = np.full(lay.S, -1, np.int32)
+    rows[lay.visual_positions()] = np.arange(lay.n_vis)
+    exp = check_kv_carried(lay.seq_offsets, rows, hidden, orig, K, V, wl.BF16)
+    plain = check_kv(hidden, orig, K, V, wl.BF16, lay)
+    np.testing.assert_array_equal(exp["idx"], plain["idx"])
+    np.testing.assert_array_equal(exp["K_out"], plain["K_out"])
+
+
+def test_prune_kv_carried_over_three_layers():
+    """Each layer runs on what the previous one kept; the survivors are the intersection of the layers' masks."""
+    rng = np.random.default_rng(960)
+    dtype, d, H, D = wl.BF16, 512, 2, 64
+    seq, rows, vis, hidden0, orig, K, V = carried_case(961, [400, 250], 600, d, H, D, dtype, vis_frac=0.9)
+    S = hidden0.shape[0]
+    o32 = wl.storage_to_f32(orig, dtype)
+    alive = np.arange(S)
+    cur_seq, cur_rows = seq, rows
+    want_alive = np.ones(S, bool)
+    for l in range(3):
+        noise = rng.standard_normal((S, d)).astype(np.float32) * (1.5 * l + rng.random((S, 1)) * 3).astype(np.float32)
+        h32 = noise.copy()
+        h32[vis] += o32[rows[vis]]
+        h_full = wl.to_storage(h32, dtype)
+        Kl = wl.to_storage(rng.standard_normal((H, S, D)).astype(np.float32), dtype)
+        full = canon.prune_kv_mapped(h_full, orig, rows, Kl, Kl, dtype, seq)
+        m = np.zeros(S, bool); m[full["idx"]] = True
+        want_alive &= m
+        exp = check_kv_carried(cur_seq, cur_rows, h_full[alive], orig, Kl[:, alive], Kl[:, alive], dtype,
+                               rope_layout=l % 2)
+        np.testing.assert_array_equal(alive[exp["idx"]], np.nonzero(want_alive)[0])
+        alive = alive[exp["idx"]]
+        cur_rows = exp["orig_row_out"]
+        cur_seq = np.concatenate([[0], np.cumsum(exp["counts"])]).astype(np.int32)
+    assert 0 < len(alive) < S
+
+
 # ----------------------------------------------------------------------------- measurement aids and event timing
 @pytest.mark.parametrize("nbytes", [16, 48, 8192, 16 * 1000003, 64 << 20])
 def test_stream_copy_and_read(nbytes):

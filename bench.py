@@ -169,6 +169,31 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_rope_layer = er[0].elapsed_time(er[1]) / (args.steps * len(layers))
 
+    # ------------------------------------------------------------------ the KV stage in its layer-to-layer form
+    # (sharpv_prune_kv_carried on the full sequence with the block map: same rows, the visual tokens found
+    # through the position -> original-row map)
+    rows_np = np.full(S, -1, np.int32)
+    rows_np[lay.visual_positions()] = np.arange(lay.n_vis, dtype=np.int32)
+    rows_dev = torch.from_numpy(rows_np).to(dev)
+    cplan = sharpv.KvCarriedPlan(lay.B, S, lay.n_vis, d, cfg.H, cfg.D, ptok, device=dev, cos=False)
+
+    def stage2_carried(i):
+        rc = cplan.run(hidden[i], orig, rows_dev, Kc[i], Vc[i], so, layers[i])
+        if rc:
+            raise RuntimeError(sharpv.status_string(rc))
+
+    for i in range(len(layers)):
+        stage2_carried(i)
+    torch.cuda.synchronize()
+    ec = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ec[0].record()
+    for _ in range(args.steps):
+        for i in range(len(layers)):
+            stage2_carried(i)
+    ec[1].record()
+    torch.cuda.synchronize()
+    ms_carried_layer = ec[0].elapsed_time(ec[1]) / (args.steps * len(layers))
+
     # ------------------------------------------------------------------ per-kernel durations (events around every launch)
     launches_per_step = 6 + 5 * len(layers)
     n_ceiling = 6
@@ -250,6 +275,10 @@ def main() -> int:
         "kv_prune_rope": {"ms_per_layer": round(ms_rope_layer, 4),
                           "alg_bytes_per_layer": int(bytes_cos + bytes_gather_rope_avg), "GBps": round(gbps_rope, 1),
                           "frac_hbm_peak": round(gbps_rope / HBM_PEAK_GBPS, 4)},
+        "kv_prune_carried": {"ms_per_layer": round(ms_carried_layer, 4),
+                             "alg_bytes_per_layer": int(bytes_stage2_avg + 4 * S + 4 * float(np.mean(kept_kv))),
+                             "GBps": round((bytes_stage2_avg + 4 * S + 4 * float(np.mean(kept_kv)))
+                                           / (ms_carried_layer * 1e-3) / 1e9, 1)},
         "tokens_per_s_whole_step": round(Nv / (ms_per_step * 1e-3), 1),
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,

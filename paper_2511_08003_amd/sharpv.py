@@ -263,6 +263,47 @@ def prune_kv(hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch
     return plan.results()
 
 
+class KvCarriedPlan:
+    """Pre-allocated outputs and workspace for `sharpv_prune_kv_carried` on one shape."""
+
+    def __init__(self, B: int, S: int, n_orig: int, d: int, H: int, D: int, params: Params, device="cuda",
+                 cos: bool = True):
+        L = load()
+        self.B, self.S, self.n_orig, self.d, self.H, self.D, self.params = B, S, n_orig, d, H, D, params
+        tdt = torch.bfloat16 if params.dtype == BF16 else torch.float32
+        self.out_idx = torch.empty(S, dtype=torch.int32, device=device)
+        self.out_count = torch.empty(B, dtype=torch.int32, device=device)
+        self.out_orig_row = torch.empty(S, dtype=torch.int32, device=device)
+        self.K_out = torch.empty((H, S, D), dtype=tdt, device=device)
+        self.V_out = torch.empty((H, S, D), dtype=tdt, device=device)
+        self.out_cos = torch.full((S,), float("nan"), dtype=torch.float32, device=device) if cos else None
+        nbytes = L.sharpv_prune_kv_carried_workspace(B, S, C.byref(params))
+        if nbytes == 0:
+            raise ValueError("sharpv_prune_kv_carried_workspace rejected the shape or the parameters")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.workspace_bytes = nbytes
+
+    def run(self, hidden: torch.Tensor, orig: torch.Tensor, orig_row: torch.Tensor, K: torch.Tensor,
+            V: torch.Tensor, seq_offsets: Optional[torch.Tensor] = None, layer: int = 0,
+            rope_cos: Optional[torch.Tensor] = None, rope_sin: Optional[torch.Tensor] = None,
+            rope_layout: int = ROPE_HALF) -> int:
+        return load().sharpv_prune_kv_carried(
+            hidden.data_ptr(), orig.data_ptr(), orig_row.data_ptr(), K.data_ptr(), V.data_ptr(), K.stride(0),
+            K.stride(1), _ptr(seq_offsets), self.B, self.S, self.n_orig, self.d, self.H, self.D, layer,
+            C.byref(self.params), self.out_idx.data_ptr(), self.out_count.data_ptr(), self.K_out.data_ptr(),
+            self.V_out.data_ptr(), self.K_out.stride(0), self.out_orig_row.data_ptr(), _ptr(self.out_cos),
+            _ptr(rope_cos), _ptr(rope_sin), 0 if rope_cos is None else rope_cos.shape[0], rope_layout,
+            self.workspace.data_ptr(), self.workspace_bytes, _stream())
+
+    def results(self) -> Dict[str, torch.Tensor]:
+        total = int(self.out_count.sum().item())
+        res = {"idx": self.out_idx[:total], "counts": self.out_count, "orig_row_out": self.out_orig_row[:total],
+               "K_out": self.K_out[:, :total, :], "V_out": self.V_out[:, :total, :]}
+        if self.out_cos is not None:
+            res["cos"] = self.out_cos
+        return res
+
+
 def prune_kv_carried(hidden: torch.Tensor, orig: torch.Tensor, orig_row: torch.Tensor, K: torch.Tensor,
                      V: torch.Tensor, seq_offsets: Optional[torch.Tensor] = None, params: Optional[Params] = None,
                      layer: int = 0, rope_cos: Optional[torch.Tensor] = None, rope_sin: Optional[torch.Tensor] = None,
@@ -270,7 +311,7 @@ def prune_kv_carried(hidden: torch.Tensor, orig: torch.Tensor, orig_row: torch.T
     """Intra-LLM stage on a sequence already thinned out by earlier layers (`sharpv_prune_kv_carried`):
     hidden [S, d], K / V [H, S, D] of the positions still alive, orig [n_orig, d], orig_row [S] int32
     (row of orig behind each position, -1 for non-visual positions).  Returns idx, counts, K_out, V_out,
-    cos (by position) and orig_row_out, the map for the next layer."""
+    cos (by position, NaN where nothing is written) and orig_row_out, the map for the next layer."""
     _require_gpu(hidden, orig, orig_row, seq_offsets, rope_cos, rope_sin)
     if not (K.is_cuda and V.is_cuda) or K.stride(2) != 1 or V.stride() != K.stride():
         raise ValueError("K and V must be GPU tensors [H, S, D] with equal strides and D contiguous")
@@ -278,31 +319,13 @@ def prune_kv_carried(hidden: torch.Tensor, orig: torch.Tensor, orig_row: torch.T
         raise ValueError("orig_row must be int32 [S]")
     if params is None:
         params = default_params(dtype_of(hidden), **over)
-    L = load()
     S, d = hidden.shape
     H, _, D = K.shape
     B = 1 if seq_offsets is None else seq_offsets.numel() - 1
-    dev = hidden.device
-    nbytes = L.sharpv_prune_kv_carried_workspace(B, S, C.byref(params))
-    if nbytes == 0:
-        raise ValueError("sharpv_prune_kv_carried_workspace rejected the shape or the parameters")
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    out_idx = torch.empty(S, dtype=torch.int32, device=dev)
-    out_count = torch.empty(B, dtype=torch.int32, device=dev)
-    out_rows = torch.empty(S, dtype=torch.int32, device=dev)
-    K_out = torch.empty((H, S, D), dtype=K.dtype, device=dev)
-    V_out = torch.empty((H, S, D), dtype=K.dtype, device=dev)
-    out_cos = torch.full((S,), float("nan"), dtype=torch.float32, device=dev)
-    check(L.sharpv_prune_kv_carried(hidden.data_ptr(), orig.data_ptr(), orig_row.data_ptr(), K.data_ptr(),
-                                    V.data_ptr(), K.stride(0), K.stride(1), _ptr(seq_offsets), B, S, orig.shape[0], d,
-                                    H, D, layer, C.byref(params), out_idx.data_ptr(), out_count.data_ptr(),
-                                    K_out.data_ptr(), V_out.data_ptr(), K_out.stride(0), out_rows.data_ptr(),
-                                    out_cos.data_ptr(), _ptr(rope_cos), _ptr(rope_sin),
-                                    0 if rope_cos is None else rope_cos.shape[0], rope_layout, ws.data_ptr(), nbytes,
-                                    _stream()), "sharpv_prune_kv_carried")
-    total = int(out_count.sum().item())
-    return {"idx": out_idx[:total], "counts": out_count, "orig_row_out": out_rows[:total], "cos": out_cos,
-            "K_out": K_out[:, :total, :], "V_out": V_out[:, :total, :]}
+    plan = KvCarriedPlan(B, S, orig.shape[0], d, H, D, params, device=hidden.device)
+    check(plan.run(hidden, orig, orig_row, K, V, seq_offsets, layer, rope_cos, rope_sin, rope_layout),
+          "sharpv_prune_kv_carried")
+    return plan.results()
 
 
 # ----------------------------------------------------------------------------- measurement aids

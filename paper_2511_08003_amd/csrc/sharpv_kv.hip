@@ -251,7 +251,11 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     __shared__ int scratch[kGatherThreads / 64];
     const int H = CH > 0 ? CH : H_any;
     const int word = blockIdx.x;
+    // With the number of heads unknown at compile time the grid's second dimension splits the head
+    // planes, one batch per workgroup (many heads would otherwise be walked by too few threads).
+    const bool first_slice = blockIdx.y == 0;
     if (word == n_words) {                       // extra workgroup: kept positions per sequence
+        if (!first_slice) return;
         if (sd.seq_offsets == nullptr) {
             const int tot = kept_before(mask16, S, scratch);
             if (threadIdx.x == 0) out_count[0] = tot;
@@ -278,7 +282,7 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
         unsigned m = mask;                       // position of the r-th kept bit
         for (int i = 0; i < r; ++i) m &= m - 1u;
         const int pos = word * kMaskWord + (__ffs(m) - 1);
-        if (q == 0) {
+        if (q == 0 && first_slice) {
             out_idx[base + r] = pos;
             if (out_orig_row != nullptr) {       // the next layer's map: the row behind each kept position
                 const int p = sd.orig_row[pos];
@@ -288,7 +292,9 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
         if (K == nullptr) continue;
         const long long src_off = (long long)pos * stride_s_bytes + (long long)q * 16;
         const long long dst_off = (long long)(base + r) * row_bytes + (long long)q * 16;
-        for (int p0 = 0; p0 < planes; p0 += kBatch) {
+        const int p_begin = CH > 0 ? 0 : (int)blockIdx.y * kBatch;
+        const int p_end = CH > 0 ? planes : (p_begin + kBatch < planes ? p_begin + kBatch : planes);
+        for (int p0 = p_begin; p0 < p_end; p0 += kBatch) {
             uint4 t[kBatch];
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {
@@ -369,7 +375,9 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     constexpr int E = Piece<T>::kElems;
     const int H = CH > 0 ? CH : H_any;
     const int word = blockIdx.x;
+    const bool first_slice = blockIdx.y == 0;    // the grid's second dimension splits the heads when CH == 0
     if (word == n_words) {                       // extra workgroup: kept positions per sequence
+        if (!first_slice) return;
         if (sd.seq_offsets == nullptr) {
             const int tot = kept_before(mask16, S, scratch);
             if (threadIdx.x == 0) out_count[0] = tot;
@@ -405,7 +413,7 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
         for (int i = 0; i < r; ++i) m &= m - 1u;
         const int bit = __ffs(m) - 1;
         const int pos = word_pos + bit;
-        if (q == 0) {
+        if (q == 0 && first_slice) {
             out_idx[base + r] = pos;
             if (out_orig_row != nullptr) {       // the next layer's map: the row behind each kept position
                 const int p = sd.orig_row[pos];
@@ -438,7 +446,9 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
         const long long dst_off = (long long)(base + r) * row_bytes + (long long)q * 16;
         const long long hop = (long long)hp * 16;
         constexpr int kHeads = CH > 0 ? (CH < 4 ? CH : 4) : 2;          // heads per batch (4 loads each)
-        for (int h0 = 0; h0 < H; h0 += kHeads) {
+        const int h_begin = CH > 0 ? 0 : (int)blockIdx.y * kHeads;
+        const int h_end = CH > 0 ? H : (h_begin + kHeads < H ? h_begin + kHeads : H);
+        for (int h0 = h_begin; h0 < h_end; h0 += kHeads) {
             uint4 kx[kHeads], ky[kHeads], vx[kHeads], vy[kHeads];
 #pragma unroll
             for (int k = 0; k < kHeads; ++k) {
@@ -482,7 +492,8 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
 template <typename T, int LAYOUT>
 static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, int n_words, size_t esz) {
 #define SHARPV_GATHER_ROPE(CH_)                                                                                     \
-    hipLaunchKernelGGL((kv_gather_rope_kernel<T, LAYOUT, CH_>), dim3(n_words + 1), dim3(kGatherThreads), 0,         \
+    hipLaunchKernelGGL((kv_gather_rope_kernel<T, LAYOUT, CH_>), dim3(n_words + 1, CH_ > 0 ? 1 : (a.H + 1) / 2),     \
+                       dim3(kGatherThreads), 0,                                                                      \
                        a.stream, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),     \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
                        (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
@@ -541,8 +552,9 @@ int launch_prune_kv(const KvArgs& a) {
     } else {
         TimedLaunch tl(kKvGather, st);
 #define SHARPV_GATHER(CH_)                                                                                          \
-    hipLaunchKernelGGL((kv_gather_kernel<CH_>), dim3(n_words + 1), dim3(kGatherThreads), 0, st, (const char*)a.K,   \
-                       (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),                                  \
+    hipLaunchKernelGGL((kv_gather_kernel<CH_>),                                                                     \
+                       dim3(n_words + 1, CH_ > 0 ? 1 : (2 * a.H + kGatherBatch - 1) / kGatherBatch),                 \
+                       dim3(kGatherThreads), 0, st, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),                                  \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
                        (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
                        a.S, a.out_idx, a.out_count, a.out_orig_row)

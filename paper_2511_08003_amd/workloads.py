@@ -267,8 +267,9 @@ def _const_rho(n: int, rho: float) -> np.ndarray:
 
 
 def config(index: int, frames_scale: float = 1.0) -> Config:
-    """The five workloads (index 1..5). `frames_scale` < 1 shrinks frame counts for quick
-    checks; 1.0 gives the stated sizes."""
+    """The five benchmark workloads (index 1..5) and the two other model shapes of the paper's
+    Table 2 (6, 7). `frames_scale` < 1 shrinks frame counts for quick checks; 1.0 gives the
+    stated sizes."""
     def nf(n: int) -> int:
         return max(2, int(round(n * frames_scale)))
 
@@ -307,7 +308,15 @@ def config(index: int, frames_scale: float = 1.0) -> Config:
             cuts.append(t)
         v = VideoSpec(n=n, rho=_const_rho(n, 0.97), cuts=tuple(cuts), seed=seed)
         return Config("c5_256f_long_bf16", BF16, 196, 3584, [v], 64, 192, 4, 128, 28, tuple(range(28)), "layer", seed)
-    raise ValueError("config index must be 1..5")
+    if index == 6:      # PLLaVA-7B shape (Table 2): 16 frames x 144 tokens, d=4096, 32 layers, 32 KV heads x 128
+        n = nf(16)
+        v = VideoSpec(n=n, rho=_const_rho(n, 0.95), cuts=tuple(range(8, n, 8)), slot_sigma=0.5, seed=seed)
+        return Config("c6_pllava7b_16f_d4096_bf16", BF16, 144, 4096, [v], 32, 96, 32, 128, 32, (16,), "layer", seed)
+    if index == 7:      # LLaVA-OneVision-0.5B shape (Table 2): 32 frames x 196 tokens, d=896, 24 layers, 2 KV heads x 64
+        n = nf(32)
+        v = VideoSpec(n=n, rho=_const_rho(n, 0.95), cuts=tuple(range(8, n, 8)), slot_sigma=0.5, seed=seed)
+        return Config("c7_llavaov05b_32f_d896_bf16", BF16, 196, 896, [v], 32, 96, 2, 64, 24, (12,), "layer", seed)
+    raise ValueError("config index must be 1..7")
 
 
 def tokens_for(cfg: Config, threads: int = 8) -> TokenWorkload:

@@ -107,7 +107,7 @@ def workloads():
     return get
 
 
-@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6, 7])
 def test_prune_tokens_on_config(workloads, index):
     cfg, tok = workloads(index)
     print(f"config {index}: {cfg.name} frames={tok.n_total} f={cfg.f} d={cfg.d}", flush=True)
@@ -116,7 +116,7 @@ def test_prune_tokens_on_config(workloads, index):
     assert 0.02 < vr < 0.9
 
 
-@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6, 7])
 def test_prune_kv_on_config(workloads, index):
     cfg, tok = workloads(index)
     lay = wl.kv_layout_for(cfg)

@@ -75,7 +75,7 @@ inline KvWorkspace carve_kv_workspace(void* base, int B, int S, int n_vis) {
     return w;
 }
 
-// The fused mean + inner-product kernel keeps three frame slabs in registers: bf16 rows only, and at
+// The fused mean + inner-product kernel keeps two packed frame slabs in registers: bf16 rows only, and at
 // most 13 rows per thread (f <= 208).  Other shapes take the two-kernel path.
 inline bool tok_uses_slab(int dtype, int f) { return dtype == SHARPV_BF16 && f <= 208; }
 inline int tok_num_slabs(int d) { return (d + kBlockElems - 1) / kBlockElems; }

@@ -4,23 +4,24 @@
 // Kernels
 //   frame_slab    (bf16, f <= 208) fused first two steps with every feature read once: a workgroup owns
 //                 one 256-column slab (= one block of the summation order) and walks a run of consecutive
-//                 frames, holding the previous, the current and the next frame's slab in registers.  Per
-//                 frame: column sums by row class -> LDS -> halving tree -> slab of the frame mean; then
-//                 per row the slab's share of x.x, x.mean and x.x_prev (one tree per row and block).
-//                 The per-slab shares are summed in ascending slab order by frame_select.
+//                 frames with two frame slabs packed in registers (the frame that arrives and the one before
+//                 it, whose registers are refilled row by row with the frame after).  One pass per frame
+//                 widens both once: column sums by row class -> LDS -> halving tree -> slab of the frame
+//                 mean, the slab's share of x.x and x.x_prev per row, and the share of x.mean of the frame
+//                 before.  The per-slab shares are summed in ascending slab order by frame_select.
 //   frame_mean    (other shapes) workgroup = (frame, 256-column slab), 32 row classes x 32 lanes: row i goes to
 //                 class i % 32, each class adds its rows in ascending order, the 32 classes are
 //                 reduced by a halving tree in LDS, divided by f.  Eq.2's average representation.
 //   token_dots    one wavefront per token row: x.x, x.mean_t and x.x_prev in the fixed order of
 //                 sharpv_device.hpp (the row, its predecessor in the previous frame and the frame
 //                 mean are streamed with 16-byte loads).
-//   frame_select  one workgroup per frame, one thread per token: Eq.1-4 from the stored inner
-//                 products, Eq.5/6 retention ratio and kept count, rank of every token by counting
-//                 (score descending, index ascending) against the scores staged in LDS, and the
-//                 frame's kept rows in ascending order.
-//   count_scan    exclusive scan of the per-frame kept counts.
+//   frame_select  one workgroup per frame: Eq.1-4 from the stored inner products, Eq.5/6 retention ratio
+//                 and kept count, rank of every token by counting 64-bit keys (score descending, index
+//                 ascending) staged in LDS, and the frame's kept rows in ascending order.
 //   token_gather  copies the kept rows into the compacted stream and writes their indices, one
-//                 wavefront per kept row.
+//                 wavefront per kept row; every workgroup scans the per-frame counts itself.
+//   count_scan    exclusive scan of the per-frame kept counts, only for batches of more frames than
+//                 token_gather stages in LDS.
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {

@@ -208,7 +208,7 @@ int sharpv_prune_kv_carried(
  * sharpv_timing_read synchronises on the recorded events and returns, for the kernel with the
  * given name, the number of timed launches and their summed duration in milliseconds.
  * Kernel names: "frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
- * "kv_cosine", "kv_mean", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read".  Not thread-safe;
+ * "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read".  Not thread-safe;
  * one device.
  */
 int sharpv_timing_enable(int max_launches);     /* creates the pool; resets earlier records */

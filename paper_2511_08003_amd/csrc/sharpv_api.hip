@@ -19,7 +19,7 @@ struct TimingPool {
 } g_timing;
 
 const char* const kKernelNames[kNumKernels] = {"frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan",
-                                               "token_gather", "kv_cosine", "kv_mean", "kv_gather",
+                                               "token_gather", "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather",
                                                "kv_gather_rope", "stream_copy", "stream_read"};
 }  // namespace
 

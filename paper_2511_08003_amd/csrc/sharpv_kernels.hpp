@@ -60,8 +60,14 @@ struct KvWorkspace {
     unsigned long long* group_mask;  // [n_groups] keep mask of 64 positions (written as 4 x 16 bits)
     int32_t* drop_seq;               // [B]
     float* cosv;                     // [n_vis]
+    int32_t* word_base;              // [n_words + 1] kept positions before each 16-bit mask word (long sequences only)
     size_t bytes;
 };
+
+// Up to this many mask words every gather workgroup adds up the popcounts of the words before its own
+// (cheap, and no extra launch); beyond it that would grow with the square of the sequence length, so a
+// scan kernel writes the prefix once.
+constexpr int kGatherSelfScanWords = 8192;
 
 inline KvWorkspace carve_kv_workspace(void* base, int B, int S, int n_vis) {
     const size_t n_groups = ((size_t)S + kGroup - 1) / kGroup;
@@ -71,6 +77,8 @@ inline KvWorkspace carve_kv_workspace(void* base, int B, int S, int n_vis) {
     w.group_mask = (unsigned long long*)(p + off);  off += align_up(n_groups * 8);
     w.drop_seq = (int32_t*)(p + off);               off += align_up((size_t)B * 4);
     w.cosv = (float*)(p + off);                     off += align_up((size_t)n_vis * 4);
+    const size_t n_words = ((size_t)S + kMaskWord - 1) / kMaskWord;
+    w.word_base = (int32_t*)(p + off);              off += align_up((n_words + 1) * 4);
     w.bytes = off;
     return w;
 }
@@ -111,7 +119,7 @@ inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d, int dty
 
 // ---------------------------------------------------------------------------- event timing
 enum KernelId { kFrameSlab = 0, kFrameMean, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
-                kKvCosine, kKvMean, kKvGather, kKvGatherRope, kStreamCopy, kStreamRead, kNumKernels };
+                kKvCosine, kKvMean, kKvMaskScan, kKvGather, kKvGatherRope, kStreamCopy, kStreamRead, kNumKernels };
 
 void timing_begin(int kernel, hipStream_t st);
 void timing_end(int kernel, hipStream_t st);

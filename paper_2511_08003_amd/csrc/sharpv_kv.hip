@@ -208,11 +208,37 @@ __global__ __launch_bounds__(64) void kv_mask_from_mean_kernel(SeqDesc sd, int S
     if (lane == 0) group_mask[group] = m;
 }
 
+// Exclusive prefix of the kept positions over the 16-bit mask words (one workgroup; used for long
+// sequences, where every gather workgroup adding up all the words before its own would be quadratic).
+__global__ __launch_bounds__(1024) void kv_mask_scan_kernel(const uint16_t* __restrict__ mask16, int n_words,
+                                                            int32_t* __restrict__ word_base) {
+    __shared__ int wave_tot[16];
+    const int tid = threadIdx.x;
+    const int seg = (n_words + 1023) / 1024;
+    const int lo = tid * seg < n_words ? tid * seg : n_words;
+    const int hi = lo + seg < n_words ? lo + seg : n_words;
+    int sum = 0;
+    for (int j = lo; j < hi; ++j) sum += __popc((unsigned)mask16[j]);
+    const int incl = block_inclusive_scan_1024(sum, wave_tot);
+    int run = incl - sum;
+    for (int j = lo; j < hi; ++j) {
+        word_base[j] = run;
+        run += __popc((unsigned)mask16[j]);
+    }
+    if (tid == 1023) word_base[n_words] = incl;
+}
+
 constexpr int kGatherThreads = 256;
 
-// Number of kept positions in [0, pos), pos <= S, summed by the whole workgroup from the 16-bit mask
-// words (every word below ceil(S/16) is complete: kv_cosine clears the bits of positions >= S).
-__device__ __forceinline__ int kept_before(const uint16_t* __restrict__ mask16, int pos, int* scratch) {
+// Number of kept positions in [0, pos), pos <= S: read from the scanned prefix when there is one, else
+// summed by the whole workgroup from the 16-bit mask words (every word below ceil(S/16) is complete:
+// kv_cosine clears the bits of positions >= S).  Called by all threads of the workgroup.
+__device__ __forceinline__ int kept_before(const uint16_t* __restrict__ mask16,
+                                           const int32_t* __restrict__ word_base, int pos, int* scratch) {
+    if (word_base != nullptr) {                  // the prefix over the words is already there
+        const int w = pos / kMaskWord, r = pos % kMaskWord;
+        return word_base[w] + (r ? __popc((unsigned)mask16[w] & ((1u << r) - 1u)) : 0);
+    }
     const int w16 = pos / kMaskWord;             // complete 16-bit words below pos
     const int w64 = w16 / 4;
     const unsigned long long* m64 = reinterpret_cast<const unsigned long long*>(mask16);
@@ -246,8 +272,8 @@ template <int CH>
 __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
     char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H_any,
-    const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S, int32_t* __restrict__ out_idx,
-    int32_t* __restrict__ out_count, int32_t* __restrict__ out_orig_row) {
+    const uint16_t* __restrict__ mask16, const int32_t* __restrict__ word_base, int n_words, SeqDesc sd, int S,
+    int32_t* __restrict__ out_idx, int32_t* __restrict__ out_count, int32_t* __restrict__ out_orig_row) {
     __shared__ int scratch[kGatherThreads / 64];
     const int H = CH > 0 ? CH : H_any;
     const int word = blockIdx.x;
@@ -257,12 +283,12 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     if (word == n_words) {                       // extra workgroup: kept positions per sequence
         if (!first_slice) return;
         if (sd.seq_offsets == nullptr) {
-            const int tot = kept_before(mask16, S, scratch);
+            const int tot = kept_before(mask16, word_base, S, scratch);
             if (threadIdx.x == 0) out_count[0] = tot;
         } else {
             for (int b = 0; b < sd.B; ++b) {
-                const int lo = kept_before(mask16, sd.seq_offsets[b], scratch);
-                const int hi = kept_before(mask16, sd.seq_offsets[b + 1], scratch);
+                const int lo = kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
+                const int hi = kept_before(mask16, word_base, sd.seq_offsets[b + 1], scratch);
                 if (threadIdx.x == 0) out_count[b] = hi - lo;
             }
         }
@@ -270,7 +296,7 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     }
     const unsigned mask = mask16[word];
     if (mask == 0u) return;                      // nothing kept here (uniform over the workgroup)
-    const int base = kept_before(mask16, word * kMaskWord, scratch);
+    const int base = kept_before(mask16, word_base, word * kMaskWord, scratch);
     const int cnt = __popc(mask);
     const int pieces = row_bytes / 16;
     const int units = cnt * pieces;              // 16-byte units of one plane of this word
@@ -368,9 +394,9 @@ template <typename T, int LAYOUT, int CH>
 __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
     char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H_any,
-    const uint16_t* __restrict__ mask16, int n_words, SeqDesc sd, int S, int32_t* __restrict__ out_idx,
-    int32_t* __restrict__ out_count, int32_t* __restrict__ out_orig_row, const float* __restrict__ rope_cos,
-    const float* __restrict__ rope_sin) {
+    const uint16_t* __restrict__ mask16, const int32_t* __restrict__ word_base, int n_words, SeqDesc sd, int S,
+    int32_t* __restrict__ out_idx, int32_t* __restrict__ out_count, int32_t* __restrict__ out_orig_row,
+    const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
     __shared__ int scratch[kGatherThreads / 64];
     constexpr int E = Piece<T>::kElems;
     const int H = CH > 0 ? CH : H_any;
@@ -379,12 +405,12 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     if (word == n_words) {                       // extra workgroup: kept positions per sequence
         if (!first_slice) return;
         if (sd.seq_offsets == nullptr) {
-            const int tot = kept_before(mask16, S, scratch);
+            const int tot = kept_before(mask16, word_base, S, scratch);
             if (threadIdx.x == 0) out_count[0] = tot;
         } else {
             for (int b = 0; b < sd.B; ++b) {
-                const int lo = kept_before(mask16, sd.seq_offsets[b], scratch);
-                const int hi = kept_before(mask16, sd.seq_offsets[b + 1], scratch);
+                const int lo = kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
+                const int hi = kept_before(mask16, word_base, sd.seq_offsets[b + 1], scratch);
                 if (threadIdx.x == 0) out_count[b] = hi - lo;
             }
         }
@@ -393,13 +419,13 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     const unsigned mask = mask16[word];
     if (mask == 0u) return;                      // nothing kept here (uniform over the workgroup)
     const int word_pos = word * kMaskWord;
-    const int base = kept_before(mask16, word_pos, scratch);
+    const int base = kept_before(mask16, word_base, word_pos, scratch);
     // sequence of the word's first position, and how many rows were kept before that sequence starts
     int b_first = 0, first_lo = 0, first_kept = 0;
     if (sd.seq_offsets != nullptr) {
         while (b_first + 1 < sd.B && sd.seq_offsets[b_first + 1] <= word_pos) ++b_first;
         first_lo = sd.seq_offsets[b_first];
-        first_kept = kept_before(mask16, first_lo, scratch);
+        first_kept = kept_before(mask16, word_base, first_lo, scratch);
     }
     const int cnt = __popc(mask);
     const int pieces = row_bytes / 16;
@@ -490,14 +516,15 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
 }
 
 template <typename T, int LAYOUT>
-static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, int n_words, size_t esz) {
+static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, const int32_t* word_base, int n_words,
+                                  size_t esz) {
 #define SHARPV_GATHER_ROPE(CH_)                                                                                     \
     hipLaunchKernelGGL((kv_gather_rope_kernel<T, LAYOUT, CH_>), dim3(n_words + 1, CH_ > 0 ? 1 : (a.H + 1) / 2),     \
                        dim3(kGatherThreads), 0,                                                                      \
                        a.stream, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),     \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
-                       (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
-                       a.S, a.out_idx, a.out_count, a.out_orig_row, a.rope_cos, a.rope_sin)
+                       (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, word_base, n_words,\
+                       a.sd, a.S, a.out_idx, a.out_count, a.out_orig_row, a.rope_cos, a.rope_sin)
     switch (a.H) {
         case 2: SHARPV_GATHER_ROPE(2); break;
         case 4: SHARPV_GATHER_ROPE(4); break;
@@ -540,14 +567,21 @@ int launch_prune_kv(const KvArgs& a) {
 
     const int n_words = (a.S + kMaskWord - 1) / kMaskWord;
     const uint16_t* mask16 = reinterpret_cast<const uint16_t*>(ws.group_mask);
+    const int32_t* word_base = nullptr;
+    if (n_words > kGatherSelfScanWords) {
+        TimedLaunch tl(kKvMaskScan, st);
+        hipLaunchKernelGGL(kv_mask_scan_kernel, dim3(1), dim3(1024), 0, st, mask16, n_words, ws.word_base);
+        word_base = ws.word_base;
+        if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
+    }
     if (a.rope_cos != nullptr) {
         TimedLaunch tl(kKvGatherRope, st);
         if (a.dtype == SHARPV_BF16) {
-            if (a.rope_layout == 0) launch_kv_gather_rope<bf16_t, 0>(a, mask16, n_words, esz);
-            else launch_kv_gather_rope<bf16_t, 1>(a, mask16, n_words, esz);
+            if (a.rope_layout == 0) launch_kv_gather_rope<bf16_t, 0>(a, mask16, word_base, n_words, esz);
+            else launch_kv_gather_rope<bf16_t, 1>(a, mask16, word_base, n_words, esz);
         } else {
-            if (a.rope_layout == 0) launch_kv_gather_rope<float, 0>(a, mask16, n_words, esz);
-            else launch_kv_gather_rope<float, 1>(a, mask16, n_words, esz);
+            if (a.rope_layout == 0) launch_kv_gather_rope<float, 0>(a, mask16, word_base, n_words, esz);
+            else launch_kv_gather_rope<float, 1>(a, mask16, word_base, n_words, esz);
         }
     } else {
         TimedLaunch tl(kKvGather, st);
@@ -556,8 +590,8 @@ int launch_prune_kv(const KvArgs& a) {
                        dim3(n_words + 1, CH_ > 0 ? 1 : (2 * a.H + kGatherBatch - 1) / kGatherBatch),                 \
                        dim3(kGatherThreads), 0, st, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),                                  \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
-                       (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, n_words, a.sd,     \
-                       a.S, a.out_idx, a.out_count, a.out_orig_row)
+                       (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, word_base, n_words,\
+                       a.sd, a.S, a.out_idx, a.out_count, a.out_orig_row)
         switch (a.H) {
             case 1: SHARPV_GATHER(1); break;
             case 2: SHARPV_GATHER(2); break;

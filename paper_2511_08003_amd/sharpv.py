@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsharpv.so")
 F32, BF16 = 0, 1
 OK = 0
 KERNEL_NAMES = ("frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
-                "kv_cosine", "kv_mean", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read")
+                "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read")
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
 
 

@@ -308,6 +308,18 @@ def test_error_codes_with_real_buffers():
     assert plan2.run(x) == 4
 
 
+def test_prune_kv_long_sequences_take_the_scanned_prefix():
+    """More than 8192 mask words (131 072 positions): the gathers read their output offsets from a scan
+    of the mask instead of adding up the words themselves."""
+    lay, hidden, orig, K, V = kv_case(730, [139000], 500, 500, 64, 1, 8, wl.BF16)
+    assert lay.S > 131072
+    check_kv(hidden, orig, K, V, wl.BF16, lay)
+    lay, hidden, orig, K, V = kv_case(731, [70000, 3, 65000], 7, 9, 64, 2, 16, wl.BF16)
+    check_kv(hidden, orig, K, V, wl.BF16, lay)
+    check_kv(hidden, orig, K, V, wl.BF16, lay, M=0.4, kv_mode=1)
+    check_kv_rope(hidden, orig, K, V, wl.BF16, lay, 0)
+
+
 # ----------------------------------------------------------------------------- rotary re-encoding in the K gather
 def rope_tables(rope_len, D, base=1e6):
     """cos / sin of delta * theta_i for a rotary embedding of the given base (float32 tables, as a model caches them)."""

@@ -10,12 +10,22 @@
 //               (only launched when the mean is asked for or decides, kv_mode 1).
 //   kv_gather   one workgroup per mask word (16 positions): output offset = popcount of the preceding
 //               mask words, rank inside the word by popcount, then batched 16-byte copies of the kept
-//               K and V rows, plane by plane.  A last workgroup writes the per-sequence counts.
+//               K and V rows, plane by plane.  One more workgroup per sequence writes that sequence's count.
 //   kv_gather_rope  the same gather with the rotary position of every kept K row re-encoded for its
 //               new place in the compacted cache (Sec. 4.1, Implementation Details).
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
+
+// Sequence that owns packed position s (0 <= s < seq_offsets[B]): the last b with seq_offsets[b] <= s.
+__device__ __forceinline__ int find_sequence(const SeqDesc& sd, int s) {
+    int lo = 0, hi = sd.B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (sd.seq_offsets[mid] <= s) lo = mid; else hi = mid;
+    }
+    return lo;
+}
 
 // Where packed position s sits: returns true and the row of `orig` when s is a visual token.
 __device__ __forceinline__ bool locate_visual(const SeqDesc& sd, int s, int* orig_row, int* seq) {
@@ -31,8 +41,7 @@ __device__ __forceinline__ bool locate_visual(const SeqDesc& sd, int s, int* ori
         *seq = 0;
         return rel >= 0 && rel < sd.n_vis;
     }
-    int b = 0;
-    while (b + 1 < sd.B && sd.seq_offsets[b + 1] <= s) ++b;
+    const int b = find_sequence(sd, s);
     const int rel = s - sd.seq_offsets[b] - sd.vis_start[b];
     const int lo = sd.vis_offsets[b];
     *orig_row = lo + rel;
@@ -267,7 +276,8 @@ constexpr int kGatherBatch = 8;     // 16-byte loads in flight per lane
 // and writes whole consecutive rows of one plane, and the planes are taken in batches with all loads
 // of a batch issued before its stores.  CH = number of heads when known at compile time (the loads
 // of a batch then carry no predicate, which is what lets them overlap); CH = 0 takes any H and
-// clamps the plane index of the loads instead of predicating them.
+// clamps the plane index of the loads instead of predicating them.  Workgroups n_words .. n_words+B-1
+// write the kept count of one sequence each.
 template <int CH>
 __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     const char* __restrict__ K, const char* __restrict__ V, long long stride_h_bytes, long long stride_s_bytes,
@@ -280,18 +290,12 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     // With the number of heads unknown at compile time the grid's second dimension splits the head
     // planes, one batch per workgroup (many heads would otherwise be walked by too few threads).
     const bool first_slice = blockIdx.y == 0;
-    if (word == n_words) {                       // extra workgroup: kept positions per sequence
+    if (word >= n_words) {                       // B extra workgroups: kept positions of one sequence each
         if (!first_slice) return;
-        if (sd.seq_offsets == nullptr) {
-            const int tot = kept_before(mask16, word_base, S, scratch);
-            if (threadIdx.x == 0) out_count[0] = tot;
-        } else {
-            for (int b = 0; b < sd.B; ++b) {
-                const int lo = kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
-                const int hi = kept_before(mask16, word_base, sd.seq_offsets[b + 1], scratch);
-                if (threadIdx.x == 0) out_count[b] = hi - lo;
-            }
-        }
+        const int b = word - n_words;
+        const int lo = sd.seq_offsets == nullptr ? 0 : kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
+        const int hi = kept_before(mask16, word_base, sd.seq_offsets == nullptr ? S : sd.seq_offsets[b + 1], scratch);
+        if (threadIdx.x == 0) out_count[b] = hi - lo;
         return;
     }
     const unsigned mask = mask16[word];
@@ -402,18 +406,12 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     const int H = CH > 0 ? CH : H_any;
     const int word = blockIdx.x;
     const bool first_slice = blockIdx.y == 0;    // the grid's second dimension splits the heads when CH == 0
-    if (word == n_words) {                       // extra workgroup: kept positions per sequence
+    if (word >= n_words) {                       // B extra workgroups: kept positions of one sequence each
         if (!first_slice) return;
-        if (sd.seq_offsets == nullptr) {
-            const int tot = kept_before(mask16, word_base, S, scratch);
-            if (threadIdx.x == 0) out_count[0] = tot;
-        } else {
-            for (int b = 0; b < sd.B; ++b) {
-                const int lo = kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
-                const int hi = kept_before(mask16, word_base, sd.seq_offsets[b + 1], scratch);
-                if (threadIdx.x == 0) out_count[b] = hi - lo;
-            }
-        }
+        const int b = word - n_words;
+        const int lo = sd.seq_offsets == nullptr ? 0 : kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
+        const int hi = kept_before(mask16, word_base, sd.seq_offsets == nullptr ? S : sd.seq_offsets[b + 1], scratch);
+        if (threadIdx.x == 0) out_count[b] = hi - lo;
         return;
     }
     const unsigned mask = mask16[word];
@@ -423,7 +421,7 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     // sequence of the word's first position, and how many rows were kept before that sequence starts
     int b_first = 0, first_lo = 0, first_kept = 0;
     if (sd.seq_offsets != nullptr) {
-        while (b_first + 1 < sd.B && sd.seq_offsets[b_first + 1] <= word_pos) ++b_first;
+        b_first = find_sequence(sd, word_pos);
         first_lo = sd.seq_offsets[b_first];
         first_kept = kept_before(mask16, word_base, first_lo, scratch);
     }
@@ -519,7 +517,7 @@ template <typename T, int LAYOUT>
 static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, const int32_t* word_base, int n_words,
                                   size_t esz) {
 #define SHARPV_GATHER_ROPE(CH_)                                                                                     \
-    hipLaunchKernelGGL((kv_gather_rope_kernel<T, LAYOUT, CH_>), dim3(n_words + 1, CH_ > 0 ? 1 : (a.H + 1) / 2),     \
+    hipLaunchKernelGGL((kv_gather_rope_kernel<T, LAYOUT, CH_>), dim3(n_words + a.B, CH_ > 0 ? 1 : (a.H + 1) / 2),     \
                        dim3(kGatherThreads), 0,                                                                      \
                        a.stream, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),     \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
@@ -587,7 +585,7 @@ int launch_prune_kv(const KvArgs& a) {
         TimedLaunch tl(kKvGather, st);
 #define SHARPV_GATHER(CH_)                                                                                          \
     hipLaunchKernelGGL((kv_gather_kernel<CH_>),                                                                     \
-                       dim3(n_words + 1, CH_ > 0 ? 1 : (2 * a.H + kGatherBatch - 1) / kGatherBatch),                 \
+                       dim3(n_words + a.B, CH_ > 0 ? 1 : (2 * a.H + kGatherBatch - 1) / kGatherBatch),                 \
                        dim3(kGatherThreads), 0, st, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),                                  \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
                        (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, word_base, n_words,\

@@ -145,6 +145,21 @@ def main() -> int:
     ms_stage2 = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
     ms_stage2_layer = ms_stage2 / len(layers)
 
+    # ------------------------------------------------------------------ the same step replayed from a captured HIP graph
+    # (the entry points only enqueue kernels, so the whole step records into one graph)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    graph.replay()
+    torch.cuda.synchronize()
+    eg = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    eg[0].record()
+    for _ in range(args.steps):
+        graph.replay()
+    eg[1].record()
+    torch.cuda.synchronize()
+    ms_graph_step = eg[0].elapsed_time(eg[1]) / args.steps
+
     # ------------------------------------------------------------------ the KV stage with rotary re-encoding of the kept K rows
     # (same step, sharpv_prune_kv_rope instead of sharpv_prune_kv; reported beside the headline, not in it)
     theta = 1e6 ** (-2.0 * np.arange(cfg.D // 2) / cfg.D)
@@ -279,6 +294,7 @@ def main() -> int:
                              "alg_bytes_per_layer": int(bytes_stage2_avg + 4 * S + 4 * float(np.mean(kept_kv))),
                              "GBps": round((bytes_stage2_avg + 4 * S + 4 * float(np.mean(kept_kv)))
                                            / (ms_carried_layer * 1e-3) / 1e9, 1)},
+        "graph_replay_ms_per_step": round(ms_graph_step, 4),
         "tokens_per_s_whole_step": round(Nv / (ms_per_step * 1e-3), 1),
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,

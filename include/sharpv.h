@@ -19,8 +19,9 @@
  *     marked "host".  The library never allocates, frees or keeps device memory; scratch space
  *     comes from the caller's workspace (query the size first).  Base pointers of feats / hidden /
  *     orig / K / V / their outputs must be 16-byte aligned, the workspace 256-byte aligned.
- *   - Calls only ENQUEUE work on `stream` (a hipStream_t passed as void*; NULL = the null stream)
- *     and return without synchronising.  Counts stay on the device, so output buffers are sized
+ *   - Calls only ENQUEUE kernels on `stream` (a hipStream_t passed as void*; NULL = the null stream)
+ *     and return without synchronising; they allocate nothing and record no memset, so a sequence
+ *     of calls can be captured into a HIP graph and replayed (with event timing switched off).  Counts stay on the device, so output buffers are sized
  *     for the worst case (everything kept).
  *   - The return value is a sharpv_status.  Argument errors are found on the host before any
  *     launch and leave every output untouched; nothing throws or aborts across this boundary.

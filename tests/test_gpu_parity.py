@@ -547,3 +547,54 @@ def test_event_timing_counts_launches():
     finally:
         sharpv.timing_disable()
     np.testing.assert_array_equal(a, b)
+
+
+# ----------------------------------------------------------------------------- capture into a HIP graph
+def test_both_stages_replay_from_a_captured_graph():
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a step can be captured once and replayed; every replay must reproduce the
+    eager results, with other work on the device between replays."""
+    tok = small_video(990, 12, 196, 1152, wl.BF16, cuts=(5,))
+    x = dev(tok.feats, wl.BF16)
+    lay, hidden, orig, K, V = kv_case(991, [700], 10, 14, 1152, 4, 128, wl.BF16)
+    hd, od, Kd, Vd = dev(hidden, wl.BF16), dev(orig, wl.BF16), dev(K, wl.BF16), dev(V, wl.BF16)
+    ct, st = rope_tables(lay.S, 128)
+    ctd, std = torch.from_numpy(ct).cuda(), torch.from_numpy(st).cuda()
+    p = sharpv.default_params(wl.BF16)
+    tplan = sharpv.TokensPlan(12, 196, 1152, p)
+    kplan = sharpv.KvPlan(1, lay.S, lay.n_vis, 1152, 4, 128, p)
+    rplan = sharpv.KvPlan(1, lay.S, lay.n_vis, 1152, 4, 128, p)
+
+    def step():
+        assert tplan.run(x) == 0
+        assert kplan.run(hd, od, Kd, Vd, int(lay.vis_start[0])) == 0
+        assert rplan.run(hd, od, Kd, Vd, int(lay.vis_start[0]), rope_cos=ctd, rope_sin=std) == 0
+
+    def snapshot():
+        torch.cuda.synchronize()
+        t, k, r = tplan.results(), kplan.results(), rplan.results()
+        return [v.clone() for v in (t["idx"], t["counts"], t["out_feats"], t["I"], k["idx"], k["K_out"], k["V_out"],
+                                    k["cos"], r["idx"], r["K_out"])]
+
+    def scribble():
+        for plan in (tplan, kplan, rplan):
+            for name in ("out_idx", "out_counts", "out_count", "out_feats", "K_out", "V_out", "out_cos", "out_scores"):
+                t = getattr(plan, name, None)
+                if t is not None:
+                    t.fill_(-1 if t.dtype == torch.int32 else 7)
+            plan.workspace.fill_(0xA5)           # the workspace carries nothing from call to call
+
+    step()
+    want = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        scribble()
+        y = (x.float() * 1.5).sum()              # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        assert float(y) == float(y)
+        for a, b in zip(want, got):
+            assert a.shape == b.shape and torch.equal(a, b)

@@ -153,6 +153,8 @@ def small_video(seed, n, f, d, dtype, rho=0.8, cuts=()):
     (9, 48, 264, wl.BF16),        # three rows per thread (odd), a second slab of one chunk
     (5, 160, 2056, wl.BF16),      # ten rows per thread (two rows left over after the four-row trees)
     (11, 112, 768, wl.BF16),      # seven rows per thread (three left over)
+    (3, 40, 65536, wl.BF16),      # the widest row: 256 slabs
+    (2, 300, 8200, wl.F32),       # two-kernel path, 33 blocks with a ragged last one
     (4100, 3, 16, wl.BF16),       # more frames than the compaction stages offsets for
     (5000, 4, 8, wl.F32),
 ])
@@ -232,6 +234,9 @@ def kv_case(seed, n_vis_per_seq, tb, ta, d, H, D, dtype, sigma_max=8.0):
     ([64], 1, 0, 896, 4, 128, wl.BF16),          # spills into a second group by one
     ([300, 5, 77], 7, 9, 1152, 2, 32, wl.F32),   # ragged batch
     ([130, 131], 0, 3, 4096, 8, 128, wl.BF16),
+    ([90, 40], 2, 2, 8200, 2, 64, wl.BF16),      # wider than the unrolled sweeps: the looped row kernel
+    ([70], 3, 3, 2056, 2, 64, wl.F32),           # float32 rows beyond four sweeps take the loop as well
+    ([50], 1, 1, 65536, 1, 8, wl.BF16),          # the widest row
 ])
 def test_prune_kv_shapes(nvs, tb, ta, d, H, D, dtype):
     lay, hidden, orig, K, V = kv_case(700 + len(nvs) + d, nvs, tb, ta, d, H, D, dtype)

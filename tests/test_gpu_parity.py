@@ -153,6 +153,10 @@ def small_video(seed, n, f, d, dtype, rho=0.8, cuts=()):
     (9, 48, 264, wl.BF16),        # three rows per thread (odd), a second slab of one chunk
     (5, 160, 2056, wl.BF16),      # ten rows per thread (two rows left over after the four-row trees)
     (11, 112, 768, wl.BF16),      # seven rows per thread (three left over)
+    (4, 80, 256, wl.BF16),        # 5, 6, 11 and 12 rows per thread of the fused kernel
+    (5, 90, 512, wl.BF16),
+    (3, 176, 264, wl.BF16),
+    (6, 192, 256, wl.BF16),
     (3, 40, 65536, wl.BF16),      # the widest row: 256 slabs
     (2, 300, 8200, wl.F32),       # two-kernel path, 33 blocks with a ragged last one
     (4100, 3, 16, wl.BF16),       # more frames than the compaction stages offsets for

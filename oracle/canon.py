@@ -35,6 +35,8 @@ def lib() -> C.CDLL:
         fp, ip, vp = C.POINTER(C.c_float), C.POINTER(C.c_int32), C.c_void_p
         L.sharpv_canon_threads.restype = C.c_int
         L.sharpv_canon_threads.argtypes = []
+        L.sharpv_canon_set_threads.restype = None
+        L.sharpv_canon_set_threads.argtypes = [C.c_int]
         L.sharpv_canon_rowdot.restype = C.c_float
         L.sharpv_canon_rowdot.argtypes = [fp, fp, C.c_int]
         L.sharpv_canon_sum32.restype = C.c_float
@@ -75,6 +77,10 @@ def _vp(a: Optional[np.ndarray]):
 
 def threads() -> int:
     return int(lib().sharpv_canon_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().sharpv_canon_set_threads(int(n))
 
 
 def rowdot(x: np.ndarray, y: np.ndarray) -> float:

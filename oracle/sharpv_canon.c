@@ -61,6 +61,15 @@ int sharpv_canon_threads(void) {
 #endif
 }
 
+/* Sets the number of threads of the outer loops (for timing the oracle on one core); n < 1 is ignored. */
+void sharpv_canon_set_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 enum { CANON_F32 = 0, CANON_BF16 = 1 };
 
 static float widen_at(const void* base, int dtype, size_t i) {

@@ -82,7 +82,7 @@ int sharpv_version(void);
  * is the total over the batch and video b owns frames [frame_offsets[b], frame_offsets[b+1]).  The
  * first frame of every video takes T := S (Eq.6); frames never look across a video boundary.
  *
- * Limits: 1 <= f <= 1024, d a positive multiple of 8, n_frames*f < 2^31, 1 <= B <= n_frames.
+ * Limits: 1 <= f <= 1024, d a positive multiple of 8 up to 65536, n_frames*f < 2^31, 1 <= B <= n_frames.
  */
 size_t sharpv_prune_tokens_workspace(int n_frames, int f, int d, const sharpv_params* params /* host */);
 
@@ -113,8 +113,8 @@ int sharpv_prune_tokens(
  * positions), D contiguous.  K_out / V_out receive [H, S_kept, D] with head stride out_stride_h
  * (>= S*D is always enough) and position stride D; they must not overlap K / V.
  *
- * Limits: d a positive multiple of 8; D*sizeof(element) and all strides*sizeof(element) multiples
- * of 16; S < 2^31.
+ * Limits: d a positive multiple of 8 up to 65536; D*sizeof(element) and all strides*sizeof(element)
+ * multiples of 16; 1 <= B <= S < 2^31; 0 <= n_vis <= S.
  */
 size_t sharpv_prune_kv_workspace(int B, int S, int n_vis, const sharpv_params* params /* host */);
 

@@ -167,6 +167,22 @@ def test_prune_tokens_shapes(n, f, d, dtype):
     check_tokens(tok.feats, dtype, None)
 
 
+def test_prune_tokens_beyond_four_gib_of_features():
+    """3100 frames of the model shape are 4.36e9 bytes: byte offsets pass 2^32 (and the frame count passes
+    what the compaction scans by itself)."""
+    n, f, d = 3100, 196, 3584
+    spec = wl.VideoSpec(n=n, rho=np.full(n, 0.9), cuts=tuple(range(50, n, 97)), seed=4242)
+    tok = wl.make_tokens([spec], f, d, wl.BF16, threads=16)
+    assert tok.feats.nbytes > 2**32
+    got = sharpv.prune_tokens(dev(tok.feats, wl.BF16))
+    torch.cuda.synchronize()
+    exp = canon.prune_tokens(tok.feats, wl.BF16, tok.frame_offsets)
+    np.testing.assert_array_equal(got["counts"].cpu().numpy(), exp["counts"])
+    np.testing.assert_array_equal(got["idx"].cpu().numpy(), exp["idx"])
+    np.testing.assert_array_equal(got["I"].cpu().numpy(), exp["I"])
+    np.testing.assert_array_equal(host(got["out_feats"], wl.BF16), exp["out_feats"])
+
+
 def test_prune_tokens_hyper_parameters():
     tok = small_video(601, 6, 128, 768, wl.BF16, rho=0.6)
     for w in (0.0, 0.5, 3.0):

@@ -623,3 +623,63 @@ def test_both_stages_replay_from_a_captured_graph():
         assert float(y) == float(y)
         for a, b in zip(want, got):
             assert a.shape == b.shape and torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------- seeded sweep over small shapes
+def test_sweep_of_small_shapes_stage_1():
+    rng = np.random.default_rng(20251127)
+    for case in range(36):
+        dtype = wl.BF16 if case % 3 else wl.F32
+        f = int(rng.choice([1, 2, 15, 16, 31, 33, 64, 97, 143, 196, 207, 208, 209, 256, 300, 577, 1024]))
+        d = 8 * int(rng.integers(1, 130))
+        B = int(rng.integers(1, 5))
+        ns = [int(rng.integers(1, 7)) for _ in range(B)]
+        specs = [wl.VideoSpec(n=n, rho=np.full(n, float(rng.uniform(0.3, 0.99))),
+                              cuts=tuple(sorted(set(int(c) for c in rng.integers(1, n, size=int(rng.integers(0, 2)))))) if n > 1 else (),
+                              seed=3000 + 10 * case + b) for b, n in enumerate(ns)]
+        tok = wl.make_tokens(specs, f, d, dtype, threads=2)
+        kw = {}
+        if case % 4 == 1:
+            kw["min_keep"] = int(rng.integers(0, f + 1))
+        if case % 4 == 2:
+            kw["w"] = float(rng.choice([0.0, 0.25, 2.0]))
+        if case % 7 == 3:
+            kw.update(mode=1, K=float(rng.uniform(0.2, 2.5)))
+        print(f"case {case}: frames {ns} f={f} d={d} dtype={dtype} {kw}", flush=True)
+        check_tokens(tok.feats, dtype, tok.frame_offsets if B > 1 else None, **kw)
+
+
+def test_sweep_of_small_shapes_stage_2():
+    rng = np.random.default_rng(20251128)
+    for case in range(36):
+        dtype = wl.BF16 if case % 3 else wl.F32
+        esz = 2 if dtype == wl.BF16 else 4
+        B = int(rng.integers(1, 5))
+        nvs = [int(rng.integers(0, 200)) for _ in range(B)]
+        tb, ta = int(rng.integers(0, 20)), int(rng.integers(0, 20))
+        if sum(nvs) + B * (tb + ta) == 0:
+            ta = 1
+        d = 8 * int(rng.integers(1, 140))
+        H = int(rng.choice([1, 2, 3, 4, 5, 8, 12]))
+        D = (32 // esz) * int(rng.integers(1, 9))            # half rows are whole 16-byte pieces (needed by the rope form)
+        lay, hidden, orig, K, V = kv_case(5000 + case, nvs, tb, ta, d, H, D, dtype)
+        M = float(rng.choice([0.2, 0.2, 0.05, 0.6]))
+        print(f"case {case}: nvs {nvs} text {tb}+{ta} d={d} H={H} D={D} dtype={dtype} M={M}", flush=True)
+        if lay.n_vis == 0:
+            orig = np.zeros((1, d), hidden.dtype)
+        kind = case % 4
+        if kind == 0:
+            check_kv(hidden, orig, K, V, dtype, lay, M=M)
+        elif kind == 1:
+            check_kv(hidden, orig, K, V, dtype, lay, M=M, kv_mode=1)
+        elif kind == 2 and lay.n_vis > 0:
+            check_kv_rope(hidden, orig, K, V, dtype, lay, int(rng.integers(0, 2)), M=M)
+        elif lay.n_vis > 0:
+            rows = np.full(lay.S, -1, np.int32)
+            rows[lay.visual_positions()] = rng.permutation(lay.n_vis).astype(np.int32)
+            vis = lay.visual_positions()
+            hidden[vis] = wl.to_storage(wl.storage_to_f32(orig, dtype)[rows[vis]]
+                                        + (rng.random((lay.n_vis, 1)) * 8).astype(np.float32)
+                                        * rng.standard_normal((lay.n_vis, d)).astype(np.float32), dtype)
+            check_kv_carried(lay.seq_offsets, rows, hidden, orig, K, V, dtype, M=M,
+                             rope_layout=int(rng.integers(0, 2)) if case % 8 == 3 else None)

@@ -9,7 +9,7 @@ Pruning", Sec. 3.2 "Information-Aware Memory Space Pruning"); equation numbers c
 displayed equations in order of appearance: Eq.1 Dissim, Eq.2 spatial importance S, Eq.3
 temporal importance T, Eq.4 score I, Eq.5 threshold_t, Eq.6 threshold_1, Eq.7 Discard(l).
 
-Readings taken where the paper is silent (each is listed with its reason in the design notes):
+Readings taken where the paper is silent:
   * thresholds of Eq.5/6 are *retention* ratios; kept count k_t = floor(r_t*f + 1/2),
     clamped to [min_keep, f];
   * the first frame of a video uses T := S (the virtual preceding frame of Sec. 3.1 whose

@@ -2,10 +2,10 @@
 // embedding, keep/discard decision, and the gather of the layer's K/V rows into a compacted cache.
 //
 // Kernels
-//   kv_cosine   one wavefront per packed position, 16 positions per workgroup.  A wavefront issues
+//   kv_cosine   one wavefront per packed position, 8 positions per workgroup.  A wavefront issues
 //               all 16-byte loads of its hidden row and original row at once (1 KB contiguous per
 //               instruction), accumulates h.h, o.o, h.o in the fixed order of sharpv_device.hpp and
-//               decides Eq.7; the workgroup leaves one 16-bit word of the keep mask.
+//               decides Eq.7; the workgroup leaves one byte of the keep mask.
 //   kv_mean     one workgroup per sequence: mean cosine of its visual tokens in a fixed order
 //               (only launched when the mean is asked for or decides, kv_mode 1).
 //   kv_gather   one workgroup per mask word (16 positions): output offset = popcount of the preceding
@@ -115,16 +115,17 @@ __device__ __forceinline__ float row_cosine_loop(const T* __restrict__ hrow, con
     return cos_from_dots(ho, hh, oo);
 }
 
-constexpr int kCosRows = kMaskWord;  // packed positions (= wavefronts) per workgroup of kv_cosine
+constexpr int kCosRows = 8;          // packed positions (= wavefronts) per workgroup of kv_cosine: one byte of the mask
 
-// One wavefront per packed position, 16 positions per workgroup.  The 16 decisions of a workgroup
-// form one 16-bit word of the keep mask; four consecutive words are the 64-bit mask of a group of
-// kGroup = 64 positions (little endian: position 64g+i is bit i of 64-bit word g).
+// One wavefront per packed position, 8 positions per workgroup (smaller workgroups keep more
+// wavefronts resident while others retire).  The 8 decisions of a workgroup form one byte of the keep
+// mask; two bytes are one 16-bit word, four words the 64-bit mask of a group of kGroup = 64 positions
+// (little endian: position 64g+i is bit i of 64-bit word g).
 template <typename T, int NS, bool FULL>
 __global__ __launch_bounds__(kCosRows * 64) void kv_cosine_kernel(const T* __restrict__ hidden,
                                                                   const T* __restrict__ orig, SeqDesc sd, int S, int d,
                                                                   float M, float* __restrict__ cos_out,   // [n_vis] or nullptr
-                                                                  uint16_t* __restrict__ mask16) {
+                                                                  uint8_t* __restrict__ mask8) {
     __shared__ int keep_flag[kCosRows];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(kCosRows * 64) void kv_cosine_kernel(const T* __res
     __syncthreads();
     if (wave == 0) {
         const unsigned long long m = __ballot(lane < kCosRows && keep_flag[lane & (kCosRows - 1)] != 0);
-        if (lane == 0) mask16[blockIdx.x] = (uint16_t)m;
+        if (lane == 0) mask8[blockIdx.x] = (uint8_t)m;
     }
 }
 
@@ -158,8 +159,9 @@ static void launch_kv_cosine(const KvArgs& a, const KvWorkspace& ws, float* cos_
     const int nchunks = a.d / kChunk;
     const int ns = (nchunks + 63) / 64;
     const bool full = nchunks == ns * 64;
-    const dim3 grid((a.S + kCosRows - 1) / kCosRows), block(kCosRows * 64);
-    uint16_t* mask16 = reinterpret_cast<uint16_t*>(ws.group_mask);
+    // both bytes of every 16-bit mask word are written (the second one may lie wholly past S: zero)
+    const dim3 grid(2 * ((a.S + kMaskWord - 1) / kMaskWord)), block(kCosRows * 64);
+    uint8_t* mask16 = reinterpret_cast<uint8_t*>(ws.group_mask);
 #define SHARPV_COS_CASE(NS_)                                                                                        \
     case NS_:                                                                                                       \
         if (full)                                                                                                   \

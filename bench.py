@@ -303,6 +303,13 @@ def main() -> int:
             traffic = rec["traffic_bytes_per_launch"]
     except Exception:
         traffic = None
+    traffic_slab = None
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "frame_slab_c5_256f_traffic.json")))
+        if rec.get("sources_sha256") == sha and rec.get("workload") == cfg.name:
+            traffic_slab = rec["traffic_bytes_per_launch"]
+    except Exception:
+        traffic_slab = None
 
     out = {
         "metric": "visual tokens/sec through score+select+compact; KV-prune GB/s vs HBM peak",
@@ -337,6 +344,10 @@ def main() -> int:
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "alg_bytes_per_launch": int(bytes_cos), "avg_launch_us": kern[dom]["avg_us"]},
+        "roofline_stage1": None if "frame_slab" not in kern else {
+            "kernel": "frame_slab", "bound": "hbm", "achieved": kern["frame_slab"]["alg_GBps"], "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(kern["frame_slab"]["alg_GBps"] / HBM_PEAK_GBPS, 4), "traffic": traffic_slab,
+            "alg_bytes_per_launch": int(Nv * row), "avg_launch_us": kern["frame_slab"]["avg_us"]},
         "kernels": kern,
         "hbm_ceiling": {"read_GBps": kern.get("stream_read", {}).get("alg_GBps"),
                         "copy_GBps": kern.get("stream_copy", {}).get("alg_GBps")},

@@ -44,9 +44,11 @@ __device__ __forceinline__ bool locate_visual(const SeqDesc& sd, int s, int* ori
     const int b = find_sequence(sd, s);
     const int rel = s - sd.seq_offsets[b] - sd.vis_start[b];
     const int lo = sd.vis_offsets[b];
-    *orig_row = lo + rel;
+    const int p = lo + rel;
+    *orig_row = p;
     *seq = b;
-    return rel >= 0 && rel < sd.vis_offsets[b + 1] - lo;
+    // the last two tests only matter for malformed descriptor arrays: no row outside orig is ever read
+    return rel >= 0 && rel < sd.vis_offsets[b + 1] - lo && p >= 0 && p < sd.n_vis;
 }
 
 // Three inner products of one (hidden row, original row) pair by one wavefront, chunk index
@@ -189,9 +191,9 @@ __global__ __launch_bounds__(64) void kv_mean_kernel(const float* __restrict__ c
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
     int lo = 0, hi = sd.n_vis;
-    if (sd.seq_offsets != nullptr) {
-        lo = sd.vis_offsets[b];
-        hi = sd.vis_offsets[b + 1];
+    if (sd.seq_offsets != nullptr) {             // clamped: malformed offsets must not reach past the cosines
+        lo = min(max(sd.vis_offsets[b], 0), sd.n_vis);
+        hi = min(max(sd.vis_offsets[b + 1], 0), sd.n_vis);
     }
     float p = 0.0f;
     if (lane < 32)
@@ -295,8 +297,13 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_kernel(
     if (word >= n_words) {                       // B extra workgroups: kept positions of one sequence each
         if (!first_slice) return;
         const int b = word - n_words;
-        const int lo = sd.seq_offsets == nullptr ? 0 : kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
-        const int hi = kept_before(mask16, word_base, sd.seq_offsets == nullptr ? S : sd.seq_offsets[b + 1], scratch);
+        int p_lo = 0, p_hi = S;
+        if (sd.seq_offsets != nullptr) {             // clamped: malformed offsets must not reach past the mask
+            p_lo = min(max(sd.seq_offsets[b], 0), S);
+            p_hi = min(max(sd.seq_offsets[b + 1], 0), S);
+        }
+        const int lo = kept_before(mask16, word_base, p_lo, scratch);
+        const int hi = kept_before(mask16, word_base, p_hi, scratch);
         if (threadIdx.x == 0) out_count[b] = hi - lo;
         return;
     }
@@ -402,7 +409,7 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     char* __restrict__ K_out, char* __restrict__ V_out, long long out_stride_h_bytes, int row_bytes, int H_any,
     const uint16_t* __restrict__ mask16, const int32_t* __restrict__ word_base, int n_words, SeqDesc sd, int S,
     int32_t* __restrict__ out_idx, int32_t* __restrict__ out_count, int32_t* __restrict__ out_orig_row,
-    const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
+    const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_len) {
     __shared__ int scratch[kGatherThreads / 64];
     constexpr int E = Piece<T>::kElems;
     const int H = CH > 0 ? CH : H_any;
@@ -411,8 +418,13 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     if (word >= n_words) {                       // B extra workgroups: kept positions of one sequence each
         if (!first_slice) return;
         const int b = word - n_words;
-        const int lo = sd.seq_offsets == nullptr ? 0 : kept_before(mask16, word_base, sd.seq_offsets[b], scratch);
-        const int hi = kept_before(mask16, word_base, sd.seq_offsets == nullptr ? S : sd.seq_offsets[b + 1], scratch);
+        int p_lo = 0, p_hi = S;
+        if (sd.seq_offsets != nullptr) {             // clamped: malformed offsets must not reach past the mask
+            p_lo = min(max(sd.seq_offsets[b], 0), S);
+            p_hi = min(max(sd.seq_offsets[b + 1], 0), S);
+        }
+        const int lo = kept_before(mask16, word_base, p_lo, scratch);
+        const int hi = kept_before(mask16, word_base, p_hi, scratch);
         if (threadIdx.x == 0) out_count[b] = hi - lo;
         return;
     }
@@ -424,7 +436,7 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
     int b_first = 0, first_lo = 0, first_kept = 0;
     if (sd.seq_offsets != nullptr) {
         b_first = find_sequence(sd, word_pos);
-        first_lo = sd.seq_offsets[b_first];
+        first_lo = min(max(sd.seq_offsets[b_first], 0), word_pos);     // clamped against malformed offsets
         first_kept = kept_before(mask16, word_base, first_lo, scratch);
     }
     const int cnt = __popc(mask);
@@ -452,11 +464,12 @@ __global__ __launch_bounds__(kGatherThreads) void kv_gather_rope_kernel(
             int b = b_first;
             while (b + 1 < sd.B && sd.seq_offsets[b + 1] <= pos) ++b;
             if (b != b_first) {                  // the sequence starts inside this word
-                seq_lo = sd.seq_offsets[b];
+                seq_lo = min(max(sd.seq_offsets[b], word_pos + 1), word_pos + kMaskWord - 1);
                 seq_kept = base + __popc(mask & ((1u << (seq_lo - word_pos)) - 1u));
             }
         }
-        const int delta = (pos - seq_lo) - (base + r - seq_kept);
+        // 0 <= delta < S <= rope_len for well-formed offsets; clamped so that no table row outside is read
+        const int delta = min(max((pos - seq_lo) - (base + r - seq_kept), 0), rope_len - 1);
         const float* ct = rope_cos + (size_t)delta * half;
         const float* st = rope_sin + (size_t)delta * half;
         // table entries of this thread's pairs: LAYOUT 0: pairs q*E .. q*E+E-1 (x in piece q, y in piece
@@ -524,7 +537,7 @@ static void launch_kv_gather_rope(const KvArgs& a, const uint16_t* mask16, const
                        a.stream, (const char*)a.K, (const char*)a.V, (long long)(a.kv_stride_h * (int64_t)esz),     \
                        (long long)(a.kv_stride_s * (int64_t)esz), (char*)a.K_out, (char*)a.V_out,                    \
                        (long long)(a.out_stride_h * (int64_t)esz), (int)(a.D * esz), a.H, mask16, word_base, n_words,\
-                       a.sd, a.S, a.out_idx, a.out_count, a.out_orig_row, a.rope_cos, a.rope_sin)
+                       a.sd, a.S, a.out_idx, a.out_count, a.out_orig_row, a.rope_cos, a.rope_sin, a.rope_len)
     switch (a.H) {
         case 2: SHARPV_GATHER_ROPE(2); break;
         case 4: SHARPV_GATHER_ROPE(4); break;

@@ -140,7 +140,7 @@ const char* sharpv_status_string(int status) {
     }
 }
 
-int sharpv_version(void) { return 100; }
+int sharpv_version(void) { return 200; }   // 0.2.0: re-encoding and carried forms of the KV call
 
 size_t sharpv_prune_tokens_workspace(int n_frames, int f, int d, const sharpv_params* params) {
     if (check_params(params) != SHARPV_OK || check_token_shape(1, n_frames, f, d) != SHARPV_OK) return 0;

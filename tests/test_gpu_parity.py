@@ -683,3 +683,37 @@ def test_sweep_of_small_shapes_stage_2():
                                         * rng.standard_normal((lay.n_vis, d)).astype(np.float32), dtype)
             check_kv_carried(lay.seq_offsets, rows, hidden, orig, K, V, dtype, M=M,
                              rope_layout=int(rng.integers(0, 2)) if case % 8 == 3 else None)
+
+
+# ----------------------------------------------------------------------------- tiny magnitudes
+def test_tiny_magnitudes_follow_the_float32_oracle():
+    """Features scaled by 2^-30 behave like the unscaled ones (every quantity is a ratio).  At 2^-60 and
+    2^-66 the products of two squared norms underflow float32: the float32 contract then gives cosine 0
+    (all scores tie, everything in the KV stage is below M) where the float64 definition does not, so only
+    the float32 oracle is the reference there."""
+    tok = small_video(995, 6, 64, 512, wl.BF16, rho=0.7)
+    base = wl.storage_to_f32(tok.feats, wl.BF16)
+    lay, hidden, orig, K, V = kv_case(996, [120], 4, 4, 512, 2, 64, wl.BF16)
+    h32, o32 = wl.storage_to_f32(hidden, wl.BF16), wl.storage_to_f32(orig, wl.BF16)
+    ref_counts = check_tokens(tok.feats, wl.BF16, None)["counts"]
+    for e in (-30, -60, -66):
+        scale = np.float32(2.0 ** e)
+        feats = wl.to_storage(base * scale, wl.BF16)
+        np.testing.assert_array_equal(wl.storage_to_f32(feats, wl.BF16), base * scale)      # exact scaling
+        hs, os_ = wl.to_storage(h32 * scale, wl.BF16), wl.to_storage(o32 * scale, wl.BF16)
+        if e == -30:
+            np.testing.assert_array_equal(check_tokens(feats, wl.BF16, None)["counts"], ref_counts)
+            check_kv(hs, os_, K, V, wl.BF16, lay)
+            continue
+        got = run_tokens(feats, wl.BF16, np.asarray([0, 6], np.int32))
+        exp = canon.prune_tokens(feats, wl.BF16, np.asarray([0, 6], np.int32))
+        assert np.all(exp["I"] == exp["I"][0, 0])                                            # everything ties
+        for k, name in (("counts", "counts"), ("idx", "idx"), ("I", "I"), ("ratio", "ratio")):
+            np.testing.assert_array_equal(got[k].cpu().numpy(), exp[name])
+        np.testing.assert_array_equal(host(got["out_feats"], wl.BF16), exp["out_feats"])
+        gk = run_kv(hs, os_, K, V, wl.BF16, lay)
+        ek = canon.prune_kv(hs, os_, K, V, wl.BF16, lay.seq_offsets, lay.vis_start, lay.vis_offsets)
+        assert np.all(ek["cos"] == 0.0) and len(ek["idx"]) == 8
+        np.testing.assert_array_equal(gk["idx"].cpu().numpy(), ek["idx"])
+        np.testing.assert_array_equal(gk["cos"].cpu().numpy(), ek["cos"])
+        np.testing.assert_array_equal(host(gk["K_out"], wl.BF16), ek["K_out"])

@@ -318,7 +318,8 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if cfg.dtype == wl.F32 else "bf16 inputs, f32 accumulation",
+        "dtype": "f32",                                   # the arithmetic type of every score and decision
+        "storage_dtype": "f32" if cfg.dtype == wl.F32 else "bf16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "frames": n, "tokens_per_frame": f, "d": d, "visual_tokens": Nv,
                    "kv_layers_per_step": len(layers), "kv_heads": cfg.H, "head_dim": cfg.D, "seq_len": S,

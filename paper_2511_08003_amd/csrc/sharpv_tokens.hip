@@ -154,6 +154,7 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
 #pragma unroll
         for (int j = 0; j < 8; ++j) { pe[j] = 0.0f; po[j] = 0.0f; }
         float am[KR];
+        float zq[(KR + 1) / 2];
         float aa_even = 0.0f, ab_even = 0.0f;
         // keep "uniform frame base + 32-bit lane offset" addressing: without this the lane offsets are
         // widened and added to the feature pointer once, outside the loop, at two registers per row
@@ -183,12 +184,9 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
             vab = live ? vab : 0.0f;
             am[k] = live ? vam : 0.0f;
             if (k & 1) {
-                const float z = tree32_quad(aa_even, ab_even, vaa, vab);
-                const bool ok = (k < KR - 1) || pair_row == 0 || last_row_valid;
-                if (qlead && ok && (store_ab || !pair_is_ab)) pp[16 * (k - 1)] = z;
+                zq[k / 2] = tree32_quad(aa_even, ab_even, vaa, vab);
             } else if (k == KR - 1) {            // odd row count: the last row alone (quarters 0 and 2 store)
-                const float z = tree32_pair(vaa, vab);
-                if (qlead && pair_row == 0 && last_row_valid && (store_ab || !pair_is_ab)) pp[16 * k] = z;
+                zq[k / 2] = tree32_pair(vaa, vab);
             } else {
                 aa_even = vaa;
                 ab_even = vab;
@@ -198,11 +196,22 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
             // sinks the column sums and the x.mean chains to the end of the step).
             if (k & 1)
                 asm volatile("" : "+v"(po[0]), "+v"(po[1]), "+v"(po[2]), "+v"(po[3]), "+v"(po[4]), "+v"(po[5]),
-                                  "+v"(po[6]), "+v"(po[7]), "+v"(am[k]));
+                                  "+v"(po[6]), "+v"(po[7]), "+v"(am[k]), "+v"(zq[k / 2]));
             else
                 asm volatile("" : "+v"(pe[0]), "+v"(pe[1]), "+v"(pe[2]), "+v"(pe[3]), "+v"(pe[4]), "+v"(pe[5]),
                                   "+v"(pe[6]), "+v"(pe[7]), "+v"(am[k]));
             __builtin_amdgcn_sched_barrier(0);
+        }
+        // The rows' x.x / x.x_prev shares are stored only now: stores between the refill loads would sit
+        // in the same in-order queue as the loads the next rows wait for.
+#pragma unroll
+        for (int k = 0; k < KR; ++k) {
+            if (k & 1) {
+                const bool ok = (k < KR - 1) || pair_row == 0 || last_row_valid;
+                if (qlead && ok && (store_ab || !pair_is_ab)) pp[16 * (k - 1)] = zq[k / 2];
+            } else if (k == KR - 1) {
+                if (qlead && pair_row == 0 && last_row_valid && (store_ab || !pair_is_ab)) pp[16 * k] = zq[k / 2];
+            }
         }
         mean_products(am, t - 1, t > t0);
         // The next step widens `curr` again (as its `prev`); make the compiler forget the widened

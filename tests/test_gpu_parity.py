@@ -489,6 +489,12 @@ def test_prune_kv_carried_shapes(seq_lens, n_orig, d, H, D, dtype):
     check_kv_carried(seq, bad, hidden, orig, K, V, dtype, M=2.0)
 
 
+def test_prune_kv_carried_on_a_long_sequence():
+    """The carried form past 131 072 positions (scanned mask prefix) with re-encoding."""
+    seq, rows, vis, hidden, orig, K, V = carried_case(955, [90000, 50001], 100000, 64, 2, 16, wl.BF16)
+    check_kv_carried(seq, rows, hidden, orig, K, V, wl.BF16, rope_layout=0)
+
+
 def test_prune_kv_carried_block_map_equals_plain_call():
     lay, hidden, orig, K, V = kv_case(950, [300, 120], 6, 10, 768, 4, 64, wl.BF16)
     rows = np.full(lay.S, -1, np.int32)

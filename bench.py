@@ -35,9 +35,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=5, help="workload 1..7 (5 = the 256-frame video; 6, 7 = other model shapes)")
     ap.add_argument("--layers", type=int, default=0, help="KV layers per step (0 = all layers of the config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--two-streams", action="store_true",
-                    help="also time the KV stage with the layer calls dealt to two streams (kernels then overlap, "
-                         "so leave it out of profiler runs that average kernel durations)")
+    ap.add_argument("--no-two-streams", dest="two_streams", action="store_false",
+                    help="skip the pass that deals the KV layer calls to two streams (its kernels overlap, so "
+                         "profiler runs that average kernel durations leave it out)")
     ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1), help="input generator threads")
     return ap.parse_args()
 

@@ -22,6 +22,7 @@
 //                 wavefront per kept row; every workgroup scans the per-frame counts itself.
 //   count_scan    exclusive scan of the per-frame kept counts, only for batches of more frames than
 //                 token_gather stages in LDS.
+#include <type_traits>
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
@@ -81,7 +82,13 @@ constexpr int kSlabThreads = 512;   // 16 row groups x 32 lanes
 // x.x_prev of frame t, and the share of x.mean of frame t-1, whose mean slab was finished at the end
 // of the previous step.  As soon as a row of `prev` has been widened its registers receive the same
 // row of frame t+1, so those loads are in flight for a whole step.  The two buffers swap roles from
-// step to step; x.mean of the run's last frame is taken after the loop.
+// step to step.
+//
+// A run starts with its own first frame and no predecessor, so its first loads are ones it needs
+// anyway.  x.x_prev of that frame is made where its predecessor already sits in registers: by the
+// run before it (same slab, ending at t1 = this run's t0), which after its last frame takes one more,
+// shorter step on frame t1 (x.x_prev of frame t1 and x.mean of frame t1-1, nothing else).  A run that
+// ends with the sequence takes x.mean of its last frame alone.
 //
 // Every lane loads from a valid address (row and chunk indices are clamped) so that no load sits
 // under a per-lane predicate; lanes past the end of a row contribute zeros to the trees, and the
@@ -143,9 +150,13 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
 #pragma unroll
     for (int j = 0; j < 8; ++j) m[j] = 0.0f;
 
-    auto step = [&](RawChunk<bf16_t> (&prev)[KR], RawChunk<bf16_t> (&curr)[KR], const int t) {
-        const bool has_next = t + 1 < t1;
-        const bool store_ab = t > 0;
+    const bool extra = t1 < n;                   // this run also makes x.x_prev of the next run's first frame
+    auto step = [&](RawChunk<bf16_t> (&prev)[KR], RawChunk<bf16_t> (&curr)[KR], const int t, auto with_prev_c,
+                    auto curr_stats_c) {
+        constexpr bool with_prev = decltype(with_prev_c)::value;       // false: the run's first frame
+        constexpr bool curr_stats = decltype(curr_stats_c)::value;     // false: the extra step (frame t1)
+        const bool has_next = with_prev && curr_stats && (t + 1 < t1 || extra);
+        const bool store_ab = with_prev && t > 0;
         const char* const nb = fbase + (size_t)(t + 1) * frame_bytes;
         float* const pp = pair_ptr + (size_t)t * f;
         // column sums: rows of class g (even k) and class g+16 (odd k), each ascending; the
@@ -170,15 +181,19 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
             }
             float a[8], b[8];
             unpack(curr[k], a);
-            unpack(prev[k], b);
-            if (k & 1) {
+            if constexpr (with_prev) unpack(prev[k], b);
+            if constexpr (curr_stats) {
+                if (k & 1) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) po[j] = po[j] + a[j];
-            } else {
+                    for (int j = 0; j < 8; ++j) po[j] = po[j] + a[j];
+                } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) pe[j] = pe[j] + a[j];
+                    for (int j = 0; j < 8; ++j) pe[j] = pe[j] + a[j];
+                }
             }
-            float vaa = chain8(a, a), vab = chain8(a, b), vam = chain8(b, m);
+            float vaa = 0.0f, vab = 0.0f, vam = 0.0f;
+            if constexpr (curr_stats) vaa = chain8(a, a);
+            if constexpr (with_prev) { vab = chain8(a, b); vam = chain8(b, m); }
             if (has_next) prev[k].q = load_stream(reinterpret_cast<const uint4*>(nb + off[k]));
             vaa = live ? vaa : 0.0f;
             vab = live ? vab : 0.0f;
@@ -208,12 +223,13 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
         for (int k = 0; k < KR; ++k) {
             if (k & 1) {
                 const bool ok = (k < KR - 1) || pair_row == 0 || last_row_valid;
-                if (qlead && ok && (store_ab || !pair_is_ab)) pp[16 * (k - 1)] = zq[k / 2];
+                if (qlead && ok && (pair_is_ab ? store_ab : curr_stats)) pp[16 * (k - 1)] = zq[k / 2];
             } else if (k == KR - 1) {
-                if (qlead && pair_row == 0 && last_row_valid && (store_ab || !pair_is_ab)) pp[16 * k] = zq[k / 2];
+                if (qlead && pair_row == 0 && last_row_valid && (pair_is_ab ? store_ab : curr_stats)) pp[16 * k] = zq[k / 2];
             }
         }
-        mean_products(am, t - 1, t > t0);
+        if constexpr (with_prev) mean_products(am, t - 1, true);
+        if constexpr (!curr_stats) return;
         // The next step widens `curr` again (as its `prev`); make the compiler forget the widened
         // copies instead of keeping eight floats per chunk alive across the step boundary.
 #pragma unroll
@@ -243,7 +259,7 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
         }
     };
 
-    // x.mean of the run's last frame, still packed in `buf`, against the mean slab just finished
+    // x.mean of the sequence's last frame, still packed in `buf`, against the mean slab just finished
     auto tail = [&](const RawChunk<bf16_t> (&buf)[KR], const int t) {
         float am[KR];
 #pragma unroll
@@ -257,30 +273,35 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
     };
 
     {
-        const char* const b0 = fbase + (size_t)(t0 > 0 ? t0 - 1 : t0) * frame_bytes;
         const char* const b1 = fbase + (size_t)t0 * frame_bytes;
-#pragma unroll
-        for (int k = 0; k < KR; ++k) A[k].q = load_stream(reinterpret_cast<const uint4*>(b0 + off[k]));
+        const char* const b2 = fbase + (size_t)(t0 + 1) * frame_bytes;
 #pragma unroll
         for (int k = 0; k < KR; ++k) B[k].q = load_stream(reinterpret_cast<const uint4*>(b1 + off[k]));
+        if (t0 + 1 < t1 || extra) {
+#pragma unroll
+            for (int k = 0; k < KR; ++k) A[k].q = load_stream(reinterpret_cast<const uint4*>(b2 + off[k]));
+        }
     }
-    int t = t0;
+    const std::true_type yes{};
+    const std::false_type no{};
+    step(A, B, t0, no, yes);                     // the run's first frame: no predecessor here
+    int t = t0 + 1;
     for (; t + 1 < t1; t += 2) {
-        step(A, B, t);                           // prev = A, curr = B; A is refilled with frame t+1
-        step(B, A, t + 1);
+        step(B, A, t, yes, yes);                 // prev = B, curr = A; B is refilled with frame t+1
+        step(A, B, t + 1, yes, yes);
     }
     if (t < t1) {
-        step(A, B, t);
-        tail(B, t);
+        step(B, A, t, yes, yes);
+        if (extra) step(A, B, t1, yes, no); else tail(A, t1 - 1);
     } else {
-        tail(A, t1 - 1);
+        if (extra) step(B, A, t1, yes, no); else tail(B, t1 - 1);
     }
 }
 
 // The (slab, frame) pairs, slab-major, are dealt out in equal contiguous runs, one per workgroup
 // (about one workgroup per compute unit): a run that crosses into the next slab continues there at
-// frame 0, which needs no predecessor, so every workgroup reads at most one frame slab beyond its
-// own share.
+// frame 0, which has no predecessor, so every workgroup reads at most one frame slab beyond its
+// own share (the first frame of the run that follows, at the very end).
 template <int KR>
 __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* __restrict__ feats, int n, int f, int d,
                                                                   int nslabs, int run_len, int run_extra,

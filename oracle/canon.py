@@ -48,8 +48,10 @@ def lib() -> C.CDLL:
         L.sharpv_canon_dissim.restype = C.c_float
         L.sharpv_canon_dissim.argtypes = [C.c_float] * 3
         L.sharpv_canon_prune_tokens.restype = C.c_long
+        L.sharpv_canon_one_minus_cos.restype = C.c_float
+        L.sharpv_canon_one_minus_cos.argtypes = [C.c_float] * 3
         L.sharpv_canon_prune_tokens.argtypes = [vp, C.c_int, ip, C.c_int, C.c_int, C.c_int, C.c_float, C.c_int,
-                                                C.c_float, C.c_int, fp, fp, fp, fp, ip, ip, ip, vp]
+                                                C.c_float, C.c_int, C.c_int, fp, fp, fp, fp, ip, ip, ip, vp]
         L.sharpv_canon_prune_kv.restype = C.c_long
         L.sharpv_canon_prune_kv.argtypes = [vp, vp, vp, vp, C.c_int, ip, ip, ip, C.c_int, C.c_int, C.c_int, C.c_int,
                                             C.c_float, C.c_int, fp, fp, ip, ip, vp, vp]
@@ -114,7 +116,7 @@ def _storage(a: np.ndarray, dtype: int) -> np.ndarray:
 
 
 def prune_tokens(feats: np.ndarray, dtype: int, frame_offsets: np.ndarray, w: float = 1.0, mode: int = 0,
-                 K: float = 1.6, min_keep: int = 0) -> Dict[str, np.ndarray]:
+                 K: float = 1.6, min_keep: int = 0, measure: int = 0) -> Dict[str, np.ndarray]:
     feats = _storage(feats, dtype)
     n_total, f, d = feats.shape
     fo = np.ascontiguousarray(frame_offsets, np.int32)
@@ -128,7 +130,7 @@ def prune_tokens(feats: np.ndarray, dtype: int, frame_offsets: np.ndarray, w: fl
     idx = np.empty(n_total * f, np.int32)
     out = np.empty((n_total * f, d), feats.dtype)
     tot = lib().sharpv_canon_prune_tokens(_vp(feats), dtype, _ip(fo), len(fo) - 1, f, d, w, mode, K, min_keep,
-                                          _fp(S), _fp(T), _fp(I), _fp(ratio), _ip(counts), _ip(offsets),
+                                          measure, _fp(S), _fp(T), _fp(I), _fp(ratio), _ip(counts), _ip(offsets),
                                           _ip(idx), _vp(out))
     if tot < 0:
         raise ValueError("sharpv_canon_prune_tokens: bad argument")

@@ -137,18 +137,29 @@ float sharpv_canon_dissim(float xy, float xx, float yy) {
     return sqrtf(fmaxf(q, 0.0f));
 }
 
+/* The rescaled cosine that Sec. 3.1 names as a possible stand-in for Eq.1 (with a fixed threshold K). */
+float sharpv_canon_one_minus_cos(float xy, float xx, float yy) {
+    return 1.0f - sharpv_canon_cos(xy, xx, yy);
+}
+
+static float measure_of(int measure, float xy, float xx, float yy) {
+    return measure == 0 ? sharpv_canon_dissim(xy, xx, yy) : sharpv_canon_one_minus_cos(xy, xx, yy);
+}
+
 /*
  * Pre-LLM stage (Sec. 3.1).  feats [n_total][f][d]; frame_offsets [B+1].
  * Outputs: S, T, I [n_total*f]; ratio [n_total]; counts [n_total]; offsets [n_total+1];
  * idx (capacity n_total*f) global row indices ascending; out_feats (capacity of feats) kept rows.
  * mode 0: adaptive ratio + top-k (ties to the lowest index); mode 1: keep iff I >= K.
+ * measure 0: S and T by Eq.1; measure 1: by one minus the cosine (mode 1 only).
  * Returns the total number of kept tokens, or -1 on a bad argument.
  */
 long sharpv_canon_prune_tokens(const void* feats, int dtype, const int32_t* frame_offsets, int B,
-                               int f, int d, float w, int mode, float K, int min_keep,
+                               int f, int d, float w, int mode, float K, int min_keep, int measure,
                                float* S, float* T, float* I, float* ratio,
                                int32_t* counts, int32_t* offsets, int32_t* idx, void* out_feats) {
     if (!feats || !frame_offsets || B < 1 || f < 1 || d < 1) return -1;
+    if (measure < 0 || measure > 1 || (measure == 1 && mode != 1)) return -1;
     const int n_total = frame_offsets[B];
     const size_t esz = dtype == CANON_F32 ? 4 : 2;
     unsigned char* is_first = (unsigned char*)calloc((size_t)n_total + 1, 1);
@@ -170,7 +181,7 @@ long sharpv_canon_prune_tokens(const void* feats, int dtype, const int32_t* fram
                 const float* x = cur + (size_t)i * d;
                 const float xx = sharpv_canon_rowdot(x, x, d);
                 const float xm = sharpv_canon_rowdot(x, mean, d);
-                const float s = sharpv_canon_dissim(xm, xx, mm);                     /* Eq.2 */
+                const float s = measure_of(measure, xm, xx, mm);                      /* Eq.2 */
                 float tv;
                 if (is_first[t]) {
                     tv = s;                                                          /* Eq.6: virtual preceding frame */
@@ -178,7 +189,7 @@ long sharpv_canon_prune_tokens(const void* feats, int dtype, const int32_t* fram
                     widen_row(feats, dtype, (size_t)(t - 1) * f + i, d, prv);
                     const float pp = sharpv_canon_rowdot(prv, prv, d);
                     const float xp = sharpv_canon_rowdot(x, prv, d);
-                    tv = sharpv_canon_dissim(xp, xx, pp);                            /* Eq.3 */
+                    tv = measure_of(measure, xp, xx, pp);                             /* Eq.3 */
                 }
                 const size_t r = (size_t)t * f + i;
                 S[r] = s;

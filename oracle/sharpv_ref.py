@@ -16,6 +16,8 @@ Readings taken where the paper is silent:
     every token is the frame mean), so Eq.6 is Eq.5 applied to that T;
   * a zero-norm vector has cosine 0 to everything;
   * top-k ties go to the lowest token index, kept tokens stay in stream order;
+  * the rescaled cosine 1 - cos that Sec. 3.1 allows in place of Eq.1 comes only together with
+    the fixed threshold K (mode 1), as the paper pairs them; S, T and I keep their roles;
   * Eq.7 is applied per visual token (kv_mode 0) or to the mean over a sequence's visual
     tokens (kv_mode 1); non-visual positions are always kept; "< M" is strict;
   * pruning carried from layer to layer (Sec. 3.2: discarded features do not propagate further)
@@ -79,16 +81,28 @@ def dissim_from_cos(c: np.ndarray) -> np.ndarray:
     return np.sqrt(np.maximum(0.0, 2.0 - 2.0 * np.asarray(c, dtype=np.float64)))
 
 
+def one_minus_cos(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """The rescaled cosine that Sec. 3.1 (Dissimilarity Computation Module) allows in place of
+    Eq.1 together with a fixed threshold K: 1 - cos(theta), in [0, 2]."""
+    return 1.0 - cosine(a, b)
+
+
+def _measure(kind: int):
+    if kind not in (0, 1):
+        raise ValueError("measure must be 0 (Eq.1) or 1 (one minus cosine)")
+    return dissim if kind == 0 else one_minus_cos
+
+
 # ----------------------------------------------------------------------------- Eq.2 - Eq.6
-def spatial_importance(frame: np.ndarray) -> np.ndarray:
+def spatial_importance(frame: np.ndarray, measure: int = 0) -> np.ndarray:
     """Eq.2: S_i = Dissim(F_t[i], mean_j F_t[j]); the mean row is broadcast over tokens."""
     mean = np.mean(np.asarray(frame, dtype=np.float64), axis=0, keepdims=True)
-    return dissim(frame, mean)
+    return _measure(measure)(frame, mean)
 
 
-def temporal_importance(frame: np.ndarray, prev: np.ndarray) -> np.ndarray:
+def temporal_importance(frame: np.ndarray, prev: np.ndarray, measure: int = 0) -> np.ndarray:
     """Eq.3: T_i = Dissim(F_t[i], F_{t-1}[i]) -- the same token slot in adjacent frames."""
-    return dissim(frame, prev)
+    return _measure(measure)(frame, prev)
 
 
 def importance(T: np.ndarray, S: np.ndarray, w: float) -> np.ndarray:
@@ -120,13 +134,17 @@ def select_topk(I: np.ndarray, k: int) -> np.ndarray:
 
 
 def prune_tokens(feats: np.ndarray, dtype: int, frame_offsets: np.ndarray, w: float = 1.0,
-                 mode: int = 0, K: float = 1.6, min_keep: int = 0) -> Dict[str, np.ndarray]:
+                 mode: int = 0, K: float = 1.6, min_keep: int = 0, measure: int = 0) -> Dict[str, np.ndarray]:
     """Pre-LLM stage over a packed batch of videos.
 
     feats [n_total, f, d] storage array; frame_offsets [B+1] cumulative frames per video.
     mode 0: adaptive ratio (Eq.5/6) + per-frame top-k; mode 1: keep token iff I >= K.
+    measure 0: S and T by Eq.1; measure 1: by one minus the cosine (only with mode 1, the
+    pairing Sec. 3.1 names).
     Returns S, T, I [n_total, f]; ratio [n_total]; counts [n_total]; offsets [n_total+1];
     idx [sum k] global row indices t*f+i ascending; out_feats = the kept rows, bit-copied."""
+    if measure == 1 and mode != 1:
+        raise ValueError("one minus cosine goes with the fixed threshold K (mode 1)")
     n_total, f, d = feats.shape
     x = widen(feats, dtype)
     S = np.zeros((n_total, f))
@@ -136,8 +154,8 @@ def prune_tokens(feats: np.ndarray, dtype: int, frame_offsets: np.ndarray, w: fl
     kept = []
     for b in range(len(frame_offsets) - 1):
         for t in range(int(frame_offsets[b]), int(frame_offsets[b + 1])):
-            S[t] = spatial_importance(x[t])
-            T[t] = S[t] if t == int(frame_offsets[b]) else temporal_importance(x[t], x[t - 1])
+            S[t] = spatial_importance(x[t], measure)
+            T[t] = S[t] if t == int(frame_offsets[b]) else temporal_importance(x[t], x[t - 1], measure)
     I = importance(T, S, w)
     for t in range(n_total):
         ratio[t] = keep_ratio(T[t])

@@ -222,6 +222,27 @@ def test_manual_mode_matches_definition():
         assert len(sb) == b["counts"].sum()
 
 
+def test_one_minus_cos_scalars_and_manual_mode_matches_definition():
+    L = canon.lib()
+    assert L.sharpv_canon_one_minus_cos(5.0, 5.0, 5.0) == 0.0
+    assert L.sharpv_canon_one_minus_cos(-5.0, 5.0, 5.0) == 2.0
+    assert L.sharpv_canon_one_minus_cos(0.0, 4.0, 9.0) == 1.0
+    assert L.sharpv_canon_one_minus_cos(1.0, 0.0, 9.0) == 1.0                # zero-norm reading
+    assert L.sharpv_canon_one_minus_cos(3.0, 4.0, 9.0) == 0.5
+    tok = _small_video(43, 6, 64, 512, wl.BF16, rho=0.2)
+    for w, K in ((1.0, 1.7), (0.0, 0.8), (1.0, 1.6)):
+        a = ref.prune_tokens(tok.feats, wl.BF16, tok.frame_offsets, w=w, mode=1, K=K, measure=1)
+        b = canon.prune_tokens(tok.feats, wl.BF16, tok.frame_offsets, w=w, mode=1, K=K, measure=1)
+        np.testing.assert_allclose(b["S"], a["S"], rtol=0, atol=2e-6)
+        np.testing.assert_allclose(b["T"], a["T"], rtol=0, atol=2e-6)
+        sa, sb = set(a["idx"].tolist()), set(b["idx"].tolist())
+        for r in sa ^ sb:
+            assert abs(a["I"].reshape(-1)[r] - K) < 1e-5
+        assert len(sb) == b["counts"].sum() and 0 < len(sb) < 6 * 64
+    with pytest.raises(ValueError):
+        canon.prune_tokens(tok.feats, wl.BF16, tok.frame_offsets, mode=0, measure=1)
+
+
 # ----------------------------------------------------------------------------- stage 2 against the definition
 def test_prune_kv_matches_definition_config1_shape():
     cfg = wl.config(1, frames_scale=0.25)            # 2 frames x 196 tokens, d=1152 fp32

@@ -279,6 +279,64 @@ def test_manual_threshold_mode():
     assert len(last) == 0                            # I <= 2 + w*2 = 4 < 10
 
 
+def test_one_minus_cos_closed_forms_and_relation_to_eq1():
+    # Sec. 3.1 (Dissimilarity Computation Module): 1 - cos as the stand-in for Eq.1
+    v = np.array([[3.0, 4.0, 0.0]])
+    assert ref.one_minus_cos(v, 2.5 * v)[0] == pytest.approx(0.0, abs=1e-15)
+    assert ref.one_minus_cos(v, np.array([[0.0, 0.0, 7.0]]))[0] == pytest.approx(1.0, abs=1e-15)
+    assert ref.one_minus_cos(v, -v)[0] == pytest.approx(2.0, rel=1e-15)
+    assert ref.one_minus_cos(v, np.zeros((1, 3)))[0] == 1.0                 # zero-norm reading: cos 0
+    # vectors theta apart: 1 - cos(theta) = 2 sin^2(theta/2) (versine), half the squared chord of Eq.1
+    rng = np.random.default_rng(21)
+    x = planar(rng, 60, 5)
+    th = rng.uniform(0, math.pi, 60)
+    y = np.stack([rot2(x[i], th[i]) * (0.2 + i) for i in range(60)])
+    np.testing.assert_allclose(ref.one_minus_cos(x, y), 2 * np.sin(th / 2) ** 2, rtol=1e-10, atol=1e-12)
+    a = rng.standard_normal((300, 48))
+    b = rng.standard_normal((300, 48))
+    np.testing.assert_allclose(ref.one_minus_cos(a, b), ref.dissim(a, b) ** 2 / 2, rtol=1e-12, atol=1e-12)
+    # not symmetric in a dropped-sign sense: turning one vector round mirrors the value about 1
+    np.testing.assert_allclose(ref.one_minus_cos(a, -b), 2.0 - ref.one_minus_cos(a, b), rtol=1e-12, atol=1e-12)
+
+
+def test_manual_mode_with_one_minus_cos():
+    rng = np.random.default_rng(22)
+    n, f, d = 5, 24, 32
+    x = _video(rng, n, f, d, rho=0.4)
+    fo = np.array([0, 2, n])                         # two videos: frames 0 and 2 take T := S
+    xs = x.astype(np.float64)
+    # scores by hand from library cosines
+    S = np.empty((n, f)); T = np.empty((n, f))
+    for t in range(n):
+        m = xs[t].mean(axis=0)
+        for i in range(f):
+            S[t, i] = 1 - xs[t, i] @ m / (np.linalg.norm(xs[t, i]) * np.linalg.norm(m))
+            if t in (0, 2):
+                T[t, i] = S[t, i]
+            else:
+                T[t, i] = 1 - xs[t, i] @ xs[t - 1, i] / (np.linalg.norm(xs[t, i]) * np.linalg.norm(xs[t - 1, i]))
+    for w, K in ((1.0, 0.8), (0.0, 0.5), (2.0, 1.2)):
+        o = ref.prune_tokens(x, 0, fo, w=w, mode=1, K=K, measure=1)
+        np.testing.assert_allclose(o["S"], S, rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(o["T"], T, rtol=1e-11, atol=1e-12)
+        I = T + w * S
+        near = np.abs(I - K) < 1e-9
+        assert not near.any()
+        assert o["idx"].tolist() == np.nonzero((I >= K).reshape(-1))[0].tolist()
+        assert o["counts"].tolist() == (I >= K).sum(axis=1).tolist()
+        np.testing.assert_array_equal(o["out_feats"], x.reshape(n * f, d)[o["idx"]])
+    # w = 0: 1 - cos = Dissim^2 / 2 is monotone in Dissim, so threshold K here keeps what sqrt(2K) keeps under Eq.1
+    for K in (0.5, 0.7, 1.0):
+        a = ref.prune_tokens(x, 0, fo, w=0.0, mode=1, K=K, measure=1)
+        b = ref.prune_tokens(x, 0, fo, w=0.0, mode=1, K=math.sqrt(2 * K), measure=0)
+        assert a["idx"].tolist() == b["idx"].tolist() and 0 < len(a["idx"]) < n * f
+    # the pairing of Sec. 3.1: the rescaled cosine comes with the fixed threshold only
+    with pytest.raises(ValueError):
+        ref.prune_tokens(x, 0, fo, mode=0, measure=1)
+    with pytest.raises(ValueError):
+        ref.prune_tokens(x, 0, fo, mode=1, measure=2)
+
+
 # ----------------------------------------------------------------------------- Eq.7
 def _kv_case(rng, n_vis, tb, ta, d, H=2, D=8):
     S = tb + n_vis + ta

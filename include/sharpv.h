@@ -44,12 +44,17 @@ typedef enum {
     SHARPV_ERR_NULL = 1,        /* a required pointer is NULL */
     SHARPV_ERR_SHAPE = 2,       /* a size is out of range or violates an alignment rule */
     SHARPV_ERR_DTYPE = 3,       /* params->dtype is not a sharpv_dtype */
-    SHARPV_ERR_PARAM = 4,       /* params->struct_size / mode / kv_mode / min_keep invalid */
+    SHARPV_ERR_PARAM = 4,       /* params->struct_size / mode / kv_mode / min_keep / measure invalid */
     SHARPV_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small */
     SHARPV_ERR_DEVICE = 6       /* a HIP call or kernel launch failed */
 } sharpv_status;
 
 typedef enum { SHARPV_F32 = 0, SHARPV_BF16 = 1 } sharpv_dtype;
+
+/* How far apart two token vectors are, for S (Eq.2) and T (Eq.3).  Sec. 3.1 (Dissimilarity
+ * Computation Module) uses Eq.1 throughout and names one stand-in, the rescaled cosine 1 - cos,
+ * to go with a fixed threshold K: SHARPV_ONE_MINUS_COS is accepted only with mode == 1. */
+typedef enum { SHARPV_DISSIM_EQ1 = 0, SHARPV_ONE_MINUS_COS = 1 } sharpv_measure;
 
 /* Hyper-parameters (Sec. 4.1, Implementation Details: adaptive setting M = 0.2, w = 1; the
  * semi-adaptive setting adds a fixed threshold K = 1.6). */
@@ -64,9 +69,10 @@ typedef struct sharpv_params {
     int32_t  min_keep;      /* lower clamp of the per-frame kept count (mode 0), 0 <= min_keep <= f */
     int32_t  kv_mode;       /* 0: Eq.7 per visual token;
                                1: Eq.7 on the mean cosine of a sequence's visual tokens (all or none) */
+    int32_t  measure;       /* sharpv_measure for S and T; SHARPV_ONE_MINUS_COS needs mode == 1 */
 } sharpv_params;
 
-/* Fills *p with the paper's defaults (bf16, w=1, M=0.2, mode 0, K=1.6, min_keep 0, kv_mode 0). */
+/* Fills *p with the paper's defaults (bf16, w=1, M=0.2, mode 0, K=1.6, min_keep 0, kv_mode 0, Eq.1). */
 int sharpv_params_default(sharpv_params* p /* host */);
 
 /* Static, NUL-terminated description of a status code. */

@@ -89,6 +89,8 @@ static int check_params(const sharpv_params* p) {
     if (p->dtype != SHARPV_F32 && p->dtype != SHARPV_BF16) return SHARPV_ERR_DTYPE;
     if (p->mode != 0 && p->mode != 1) return SHARPV_ERR_PARAM;
     if (p->kv_mode != 0 && p->kv_mode != 1) return SHARPV_ERR_PARAM;
+    if (p->measure != SHARPV_DISSIM_EQ1 && p->measure != SHARPV_ONE_MINUS_COS) return SHARPV_ERR_PARAM;
+    if (p->measure == SHARPV_ONE_MINUS_COS && p->mode != 1) return SHARPV_ERR_PARAM;   // pairing of Sec. 3.1
     if (p->min_keep < 0) return SHARPV_ERR_PARAM;
     if (!(p->w == p->w) || !(p->M == p->M) || !(p->K == p->K)) return SHARPV_ERR_PARAM;   // NaN
     return SHARPV_OK;
@@ -124,6 +126,7 @@ int sharpv_params_default(sharpv_params* p) {
     p->K = 1.6f;
     p->min_keep = 0;
     p->kv_mode = 0;
+    p->measure = SHARPV_DISSIM_EQ1;
     return SHARPV_OK;
 }
 
@@ -140,7 +143,7 @@ const char* sharpv_status_string(int status) {
     }
 }
 
-int sharpv_version(void) { return 200; }   // 0.2.0: re-encoding and carried forms of the KV call
+int sharpv_version(void) { return 300; }   // 0.3.0: sharpv_params grew the `measure` field
 
 size_t sharpv_prune_tokens_workspace(int n_frames, int f, int d, const sharpv_params* params) {
     if (check_params(params) != SHARPV_OK || check_token_shape(1, n_frames, f, d) != SHARPV_OK) return 0;
@@ -170,7 +173,7 @@ int sharpv_prune_tokens(const void* feats, const int32_t* frame_offsets, int B, 
     TokArgs a;
     a.feats = feats; a.frame_offsets = frame_offsets;
     a.B = B; a.n = n_frames; a.f = f; a.d = d;
-    a.dtype = params->dtype; a.mode = params->mode; a.min_keep = params->min_keep;
+    a.dtype = params->dtype; a.mode = params->mode; a.min_keep = params->min_keep; a.measure = params->measure;
     a.w = params->w; a.K = params->K;
     a.out_idx = out_idx; a.out_counts = out_counts; a.out_offsets = out_offsets;
     a.out_feats = out_feats; a.out_scores = out_scores; a.out_ratio = out_ratio;

@@ -193,6 +193,12 @@ __device__ __forceinline__ float dissim_from_dots(float xy, float xx, float yy) 
     return __builtin_sqrtf(fmaxf(q, 0.0f));
 }
 
+// S and T of Sec. 3.1 from the three inner products: Eq.1, or (measure 1) the rescaled cosine 1 - cos
+// that the same section allows together with a fixed threshold.
+__device__ __forceinline__ float measure_from_dots(int measure, float xy, float xx, float yy) {
+    return measure == 0 ? dissim_from_dots(xy, xx, yy) : 1.0f - cos_from_dots(xy, xx, yy);
+}
+
 // Inclusive integer prefix sum over a 1024-thread workgroup: shuffle scan inside each wavefront,
 // the 16 wavefront totals through LDS.  (Integers: any order gives the same sums.)
 __device__ __forceinline__ int block_inclusive_scan_1024(int v, int* wave_tot /* LDS [16] */) {

@@ -45,7 +45,7 @@ struct KvArgs {
 struct TokArgs {
     const void* feats;
     const int32_t* frame_offsets;   // device [B+1] or nullptr
-    int B, n, f, d, dtype, mode, min_keep;
+    int B, n, f, d, dtype, mode, min_keep, measure;
     float w, K;
     int32_t* out_idx; int32_t* out_counts; int32_t* out_offsets;
     void* out_feats;

@@ -380,6 +380,7 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
                                                             int nparts, size_t part_stride,
                                                             const int32_t* __restrict__ frame_offsets, int B,
                                                             int f, int d, float w, int mode, float Kthr, int min_keep,
+                                                            int measure,   // 0: Eq.1; 1: one minus cosine
                                                             int tpp,   // threads per copy of the frame (multiple of 64, >= f)
                                                             int32_t* __restrict__ local_idx,
                                                             int32_t* __restrict__ out_counts,
@@ -480,8 +481,8 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
     // Eq.1-4 per token
     float score = 0.0f;
     if (owner) {
-        const float S = dissim_from_dots(xm, xx, mm);                        // Eq.2
-        const float T = first ? S : dissim_from_dots(xp, xx, pp);            // Eq.3 (Eq.6 on a first frame)
+        const float S = measure_from_dots(measure, xm, xx, mm);              // Eq.2
+        const float T = first ? S : measure_from_dots(measure, xp, xx, pp);  // Eq.3 (Eq.6 on a first frame)
         score = __builtin_fmaf(w, S, T);                                     // Eq.4
         // Ranking key: the float's bits mapped to an unsigned integer of the same order (inputs are
         // finite, and adding +0 folds -0 into +0 so that equal scores give equal keys), the inverted
@@ -721,7 +722,7 @@ int launch_prune_tokens(const TokArgs& a) {
         hipLaunchKernelGGL(frame_select_kernel, dim3(a.n), dim3(tpp * parts), 0, st,
                            fused ? (const float*)nullptr : (const float*)ws.mean, (const float*)ws.part_mm,
                            (const float*)ws.aa, (const float*)ws.am, (const float*)ws.ab, ws.nparts, (size_t)n_rows,
-                           a.frame_offsets, a.B, a.f, a.d, a.w, a.mode, a.K, a.min_keep, tpp, ws.local_idx, a.out_counts,
+                           a.frame_offsets, a.B, a.f, a.d, a.w, a.mode, a.K, a.min_keep, a.measure, tpp, ws.local_idx, a.out_counts,
                            a.out_scores, a.out_ratio);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;

@@ -21,12 +21,14 @@ OK = 0
 KERNEL_NAMES = ("frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
                 "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read")
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
+DISSIM_EQ1, ONE_MINUS_COS = 0, 1
 
 
 class Params(C.Structure):
     """Mirror of `sharpv_params`."""
     _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32), ("w", C.c_float), ("M", C.c_float),
-                ("mode", C.c_int32), ("K", C.c_float), ("min_keep", C.c_int32), ("kv_mode", C.c_int32)]
+                ("mode", C.c_int32), ("K", C.c_float), ("min_keep", C.c_int32), ("kv_mode", C.c_int32),
+                ("measure", C.c_int32)]
 
 
 _lib: Optional[C.CDLL] = None

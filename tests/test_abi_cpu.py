@@ -37,8 +37,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_defaults_are_the_papers(lib):
     p = sharpv.default_params()
-    assert p.struct_size == C.sizeof(sharpv.Params) == 32
-    assert (p.dtype, p.mode, p.min_keep, p.kv_mode) == (sharpv.BF16, 0, 0, 0)
+    assert p.struct_size == C.sizeof(sharpv.Params) == 36
+    assert (p.dtype, p.mode, p.min_keep, p.kv_mode, p.measure) == (sharpv.BF16, 0, 0, 0, sharpv.DISSIM_EQ1)
     assert p.w == 1.0 and abs(p.M - 0.2) < 1e-7 and abs(p.K - 1.6) < 1e-6
     assert lib.sharpv_version() >= 100
     assert sharpv.status_string(0) == "ok" and "workspace" in sharpv.status_string(5)
@@ -84,6 +84,12 @@ def test_prune_tokens_rejects_bad_arguments_on_the_host(lib):
     q = sharpv.default_params(); q.min_keep = 17
     assert _tok_call(lib, q) == 4
     q = sharpv.default_params(); q.w = float("nan")
+    assert _tok_call(lib, q) == 4
+    q = sharpv.default_params(); q.measure = sharpv.ONE_MINUS_COS      # goes with the fixed threshold only
+    assert _tok_call(lib, q) == 4
+    q.mode = 1
+    assert _tok_call(lib, q, feats=None) == 1                         # accepted as parameters: next check fires
+    q.measure = 2
     assert _tok_call(lib, q) == 4
     assert lib.sharpv_prune_tokens(0x1000, None, 1, 4, 16, 64, None, 0x2000, 0x3000, 0x4000, 0x5000, None, None,
                                    0x10000, 1 << 30, None) == 1

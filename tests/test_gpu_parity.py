@@ -46,7 +46,7 @@ def check_tokens(feats, dtype, frame_offsets, ref_frames=None, **over):
     """Runs the GPU path and both oracles; returns the canonical-oracle result."""
     n, f, d = feats.shape
     offs = np.asarray([0, n] if frame_offsets is None else frame_offsets, np.int32)
-    kw = {k: over[k] for k in ("w", "mode", "K", "min_keep") if k in over}
+    kw = {k: over[k] for k in ("w", "mode", "K", "min_keep", "measure") if k in over}
     got = run_tokens(feats, dtype, offs, **kw)
     exp = canon.prune_tokens(feats, dtype, offs, **kw)
     np.testing.assert_array_equal(got["counts"].cpu().numpy(), exp["counts"])
@@ -191,6 +191,26 @@ def test_prune_tokens_hyper_parameters():
     check_tokens(tok.feats, wl.BF16, None, min_keep=128)
     for K in (0.5, 1.2, 1.6, 9.0):
         check_tokens(tok.feats, wl.BF16, None, mode=1, K=K)
+
+
+def test_prune_tokens_one_minus_cosine_with_fixed_threshold():
+    """Sec. 3.1: the rescaled cosine in place of Eq.1, together with the fixed threshold K."""
+    tok = small_video(604, 9, 196, 896, wl.BF16, rho=0.5)
+    kept = []
+    for w, K in ((1.0, 0.4), (1.0, 1.4), (1.0, 1.5), (0.0, 0.5), (2.5, 2.9)):
+        exp = check_tokens(tok.feats, wl.BF16, [0, 4, 9], mode=1, K=K, w=w, measure=1)
+        kept.append(int(exp["counts"].sum()))
+    assert kept[0] == 9 * 196 and 0 < kept[1] < kept[0] and kept[2] <= kept[1]
+    tok = small_video(605, 5, 144, 1152, wl.F32, rho=0.8)              # the two-pass kernels
+    exp = check_tokens(tok.feats, wl.F32, None, mode=1, K=1.1, measure=1)
+    assert 0 < exp["counts"].sum() < 5 * 144
+    # static and negated frames: 1 - cos is exactly 0 and exactly 2
+    rng = np.random.default_rng(606)
+    F = wl.f32_to_bf16_bits(rng.standard_normal((64, 512)).astype(np.float32))
+    exp = check_tokens(np.stack([F, F, F ^ np.uint16(0x8000)]), wl.BF16, None, mode=1, K=2.0, w=0.0, measure=1)
+    assert exp["counts"].tolist() == [0, 0, 64]
+    with pytest.raises(ValueError):
+        sharpv.prune_tokens(dev(tok.feats, wl.F32), measure=1)         # adaptive mode: refused
 
 
 def test_prune_tokens_static_negated_tied_and_ragged():

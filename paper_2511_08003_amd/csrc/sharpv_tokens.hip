@@ -94,13 +94,17 @@ constexpr int kSlabThreads = 512;   // 16 row groups x 32 lanes
 // under a per-lane predicate; lanes past the end of a row contribute zeros to the trees, and the
 // one row per thread that may lie past the frame is zeroed before it enters the column sums.
 constexpr int kSlabRowLds = kBlockElems + kBlockChunks;   // a 256-column row in LDS plus its pad words
+constexpr int kSlabWindow = 16;                           // frames whose shares wait in LDS before they are written
+constexpr int kSlabStage = kSlabWindow * 208 + 64;        // a window of frames (f <= 208) plus the row slots past the last
+constexpr int kSlabStageTotal = 256 + 3 * kSlabStage;     // a spare row, then x.x, x.x_prev, x.mean
 
 template <int KR>
 __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const int n, const int f, const int d,
                                          const int nslabs, const int slab, const int t0, const int t1,
                                          float* __restrict__ part_aa, float* __restrict__ part_am,
                                          float* __restrict__ part_ab, float* __restrict__ part_mm,
-                                         float (&sm)[16][kSlabRowLds], float (&smean)[kSlabRowLds]) {
+                                         float (&sm)[16][kSlabRowLds], float (&smean)[kSlabRowLds],
+                                         float (&sstage)[kSlabStageTotal]) {
     const int tid = threadIdx.x;
     const int l = tid & 31;
     const int g = tid >> 5;
@@ -131,17 +135,62 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
     // x.mean of rows k .. k+3 -> quarters 0..3 hold am[k], am[k+2], am[k+1], am[k+3]
     const int mean_row = (quarter & 1) * 2 + (quarter >> 1);
     float* const mean_ptr = part_am + (size_t)slab * N + g + 16 * mean_row;
+    // Where the same values wait in LDS: the shares of a window of frames are kept there and written
+    // out together (see flush below).  Lanes that hold no result write to a spare row, so that these
+    // writes need no lane mask.  Slot j of the window is frame w0 + j for x.x and x.x_prev and frame
+    // w0 + j - 1 for x.mean (which a step makes one frame late).
+    const int stage_arr = 256 + (pair_is_ab ? kSlabStage : 0);
+    const int stage_pair0 = qlead ? stage_arr + g + 16 * pair_row : g;
+    const int stage_last0 = qlead && pair_row == 0 ? stage_arr + g : g;
+    const int stage_mean0 = qlead ? 256 + 2 * kSlabStage + g + 16 * mean_row : g;
+    const int stage_step = qlead ? f : 0;        // the spare row does not move with the window slot
+    const int stage_last_step = qlead && pair_row == 0 ? f : 0;
+    int w0 = t0;                                 // first frame of the window
+    int wj = 0;                                  // frames in the window so far
+    float* stage_pair = sstage + stage_pair0;
+    float* stage_last = sstage + stage_last0;
+    float* stage_mean = sstage + stage_mean0;
+
+    // Writes the window's shares to memory, whole lines at a time, and starts the next window.  Every
+    // staging write of the window lies before a barrier of the column phase that all threads have
+    // passed.  In the first window of a run, slot 0 holds no x.x_prev (the run before makes it) and no
+    // x.mean (there is no earlier frame here).
+    auto flush = [&]() {
+        const int cnt = wj * f;
+        const int lo = w0 == t0 ? f : 0;
+        const size_t base = (size_t)slab * N + (size_t)w0 * f;
+        for (int i = tid; i < cnt; i += kSlabThreads) {
+            part_aa[base + i] = sstage[256 + i];
+            if (i >= lo) {
+                part_ab[base + i] = sstage[256 + kSlabStage + i];
+                part_am[base + i - f] = sstage[256 + 2 * kSlabStage + i];
+            }
+        }
+        __syncthreads();                         // before the slots are written again
+        w0 += wj;
+        wj = 0;
+        stage_pair = sstage + stage_pair0;
+        stage_last = sstage + stage_last0;
+        stage_mean = sstage + stage_mean0;
+    };
 
     // Trees and stores of the x.mean shares of frame tm (four rows per tree, zero padding at the end).
-    auto mean_products = [&](const float (&am)[KR], const int tm, const bool store) {
+    // staged = true: into the workgroup's staging rows (written out in whole lines during the column
+    // phase); staged = false: straight to memory.
+    auto mean_products = [&](const float (&am)[KR], const int tm, auto staged_c) {
+        constexpr bool staged = decltype(staged_c)::value;
         float* const pm = mean_ptr + (size_t)tm * f;
 #pragma unroll
         for (int k = 0; k < KR; k += 4) {
             const float z = tree32_quad(am[k], k + 1 < KR ? am[k + 1] : 0.0f, k + 2 < KR ? am[k + 2] : 0.0f,
                                         k + 3 < KR ? am[k + 3] : 0.0f);
             const int r = k + mean_row;          // this lane's row slot
-            const bool ok = (k + 3 < KR - 1) || (r < KR - 1) || (r == KR - 1 && last_row_valid);
-            if (store && qlead && ok) pm[16 * k] = z;
+            if constexpr (staged) {
+                stage_mean[16 * k] = z;
+            } else {
+                const bool ok = (k + 3 < KR - 1) || (r < KR - 1) || (r == KR - 1 && last_row_valid);
+                if (qlead && ok) pm[16 * k] = z;
+            }
         }
     };
 
@@ -155,9 +204,11 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
                     auto curr_stats_c) {
         constexpr bool with_prev = decltype(with_prev_c)::value;       // false: the run's first frame
         constexpr bool curr_stats = decltype(curr_stats_c)::value;     // false: the extra step (frame t1)
-        const bool has_next = with_prev && curr_stats && (t + 1 < t1 || extra);
+        // A full step always refills (past the sequence's end: its last frame once more, never used), so
+        // that the loads sit under no condition.
+        constexpr bool has_next = with_prev && curr_stats;
         const bool store_ab = with_prev && t > 0;
-        const char* const nb = fbase + (size_t)(t + 1) * frame_bytes;
+        const char* const nb = fbase + (size_t)(t + 1 < n ? t + 1 : n - 1) * frame_bytes;
         float* const pp = pair_ptr + (size_t)t * f;
         // column sums: rows of class g (even k) and class g+16 (odd k), each ascending; the
         // stride-16 level of the class tree adds the two right here
@@ -194,7 +245,7 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
             float vaa = 0.0f, vab = 0.0f, vam = 0.0f;
             if constexpr (curr_stats) vaa = chain8(a, a);
             if constexpr (with_prev) { vab = chain8(a, b); vam = chain8(b, m); }
-            if (has_next) prev[k].q = load_stream(reinterpret_cast<const uint4*>(nb + off[k]));
+            if constexpr (has_next) prev[k].q = load_stream(reinterpret_cast<const uint4*>(nb + off[k]));
             vaa = live ? vaa : 0.0f;
             vab = live ? vab : 0.0f;
             am[k] = live ? vam : 0.0f;
@@ -217,19 +268,34 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
                                   "+v"(pe[6]), "+v"(pe[7]), "+v"(am[k]));
             __builtin_amdgcn_sched_barrier(0);
         }
-        // The rows' x.x / x.x_prev shares are stored only now: stores between the refill loads would sit
-        // in the same in-order queue as the loads the next rows wait for.
+        // The shares leave the thread only now, after the refill loads.  A full step hands them to the
+        // window in LDS: stores that mingle with the stream of loads, even as whole lines, cost several
+        // microseconds per launch; one burst of stores per window (normally: per run) costs about half.
+        const std::true_type staged{};
+        const std::false_type direct{};
+        if constexpr (curr_stats) {
 #pragma unroll
-        for (int k = 0; k < KR; ++k) {
-            if (k & 1) {
-                const bool ok = (k < KR - 1) || pair_row == 0 || last_row_valid;
-                if (qlead && ok && (pair_is_ab ? store_ab : curr_stats)) pp[16 * (k - 1)] = zq[k / 2];
-            } else if (k == KR - 1) {
-                if (qlead && pair_row == 0 && last_row_valid && (pair_is_ab ? store_ab : curr_stats)) pp[16 * k] = zq[k / 2];
+            for (int k = 0; k < KR; ++k) {
+                if (k & 1) {
+                    stage_pair[16 * (k - 1)] = zq[k / 2];
+                } else if (k == KR - 1) {
+                    stage_last[16 * k] = zq[k / 2];
+                }
             }
+            if constexpr (with_prev) mean_products(am, t - 1, staged);
+        } else {
+#pragma unroll
+            for (int k = 0; k < KR; ++k) {
+                if (k & 1) {
+                    const bool ok = (k < KR - 1) || pair_row == 0 || last_row_valid;
+                    if (qlead && ok && pair_is_ab && store_ab) pp[16 * (k - 1)] = zq[k / 2];
+                } else if (k == KR - 1) {
+                    if (qlead && pair_row == 0 && last_row_valid && pair_is_ab && store_ab) pp[16 * k] = zq[k / 2];
+                }
+            }
+            mean_products(am, t - 1, direct);
+            return;
         }
-        if constexpr (with_prev) mean_products(am, t - 1, true);
-        if constexpr (!curr_stats) return;
         // The next step widens `curr` again (as its `prev`); make the compiler forget the widened
         // copies instead of keeping eight floats per chunk alive across the step boundary.
 #pragma unroll
@@ -257,6 +323,11 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
             const float v = tree32(live ? mm : 0.0f);
             if (tid == 0) part_mm[(size_t)t * nslabs + slab] = v;
         }
+        ++wj;
+        stage_pair += stage_step;
+        stage_last += stage_last_step;
+        stage_mean += stage_step;
+        if (wj == kSlabWindow) flush();
     };
 
     // x.mean of the sequence's last frame, still packed in `buf`, against the mean slab just finished
@@ -269,18 +340,16 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
             const float vam = chain8(b, m);
             am[k] = live ? vam : 0.0f;
         }
-        mean_products(am, t, true);
+        mean_products(am, t, std::false_type{});
     };
 
     {
         const char* const b1 = fbase + (size_t)t0 * frame_bytes;
-        const char* const b2 = fbase + (size_t)(t0 + 1) * frame_bytes;
+        const char* const b2 = fbase + (size_t)(t0 + 1 < n ? t0 + 1 : n - 1) * frame_bytes;
 #pragma unroll
         for (int k = 0; k < KR; ++k) B[k].q = load_stream(reinterpret_cast<const uint4*>(b1 + off[k]));
-        if (t0 + 1 < t1 || extra) {
 #pragma unroll
-            for (int k = 0; k < KR; ++k) A[k].q = load_stream(reinterpret_cast<const uint4*>(b2 + off[k]));
-        }
+        for (int k = 0; k < KR; ++k) A[k].q = load_stream(reinterpret_cast<const uint4*>(b2 + off[k]));
     }
     const std::true_type yes{};
     const std::false_type no{};
@@ -296,6 +365,7 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
     } else {
         if (extra) step(B, A, t1, yes, no); else tail(B, t1 - 1);
     }
+    if (wj > 0) flush();
 }
 
 // The (slab, frame) pairs, slab-major, are dealt out in equal contiguous runs, one per workgroup
@@ -313,6 +383,7 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
     // consecutive words and the other lanes' over distinct LDS banks
     __shared__ float sm[16][kSlabRowLds];        // column sums of classes g and g+16 already added
     __shared__ float smean[kSlabRowLds];
+    __shared__ float sstage[kSlabStageTotal];    // a window of frames' x.x, x.x_prev, x.mean shares on their way out
     // runs of run_len pairs, the first run_extra of them one pair longer
     const int w = blockIdx.x;
     long long u = (long long)w * run_len + (w < run_extra ? w : run_extra);   // nslabs * n may pass 2^31
@@ -321,7 +392,7 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
         const int slab = (int)(u / n);
         const int t0 = (int)(u - (long long)slab * n);
         const int t1 = (long long)t0 + (u_end - u) < n ? t0 + (int)(u_end - u) : n;
-        slab_run<KR>(feats, n, f, d, nslabs, slab, t0, t1, part_aa, part_am, part_ab, part_mm, sm, smean);
+        slab_run<KR>(feats, n, f, d, nslabs, slab, t0, t1, part_aa, part_am, part_ab, part_mm, sm, smean, sstage);
         u += t1 - t0;
     }
 }

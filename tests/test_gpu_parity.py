@@ -161,6 +161,10 @@ def small_video(seed, n, f, d, dtype, rho=0.8, cuts=()):
     (2, 300, 8200, wl.F32),       # two-kernel path, 33 blocks with a ragged last one
     (4100, 3, 16, wl.BF16),       # more frames than the compaction stages offsets for
     (5000, 4, 8, wl.F32),
+    (4096, 4, 256, wl.BF16),      # fused kernel, 16 frames per workgroup on 256 compute units: exactly one window of shares
+    (4352, 5, 256, wl.BF16),      # 17 per workgroup: a full window and one frame more
+    (8448, 3, 256, wl.BF16),      # 33: two windows and one
+    (2100, 6, 512, wl.BF16),      # two slabs, runs of 16-17 frames, one of them across the slab boundary
 ])
 def test_prune_tokens_shapes(n, f, d, dtype):
     tok = small_video(500 + n * 7 + f, n, f, d, dtype, cuts=(n // 2,) if n > 2 else ())

@@ -675,6 +675,9 @@ def test_sweep_of_small_shapes_stage_1():
             kw["w"] = float(rng.choice([0.0, 0.25, 2.0]))
         if case % 7 == 3:
             kw.update(mode=1, K=float(rng.uniform(0.2, 2.5)))
+        if case % 7 == 5:                                            # the fixed threshold on 1 - cos (own stream of draws)
+            kw = dict(mode=1, measure=1, K=float(np.random.default_rng(77 + case).uniform(0.1, 1.9)),
+                      w=kw.get("w", 1.0))
         print(f"case {case}: frames {ns} f={f} d={d} dtype={dtype} {kw}", flush=True)
         check_tokens(tok.feats, dtype, tok.frame_offsets if B > 1 else None, **kw)
 

@@ -28,6 +28,8 @@
  *   - Inputs must be finite.  Scores are accumulated in float32 in a fixed order, so results do
  *     not depend on launch geometry and repeat bit for bit.
  *   - Overlapping calls that share a workspace race; calls on one stream are ordered.
+ *   - The pruning calls keep no state of their own: host threads may call them at the same time, each
+ *     with its own workspace and outputs.  The event-timing calls are the exception (see there).
  */
 #ifndef SHARPV_H
 #define SHARPV_H

@@ -727,14 +727,15 @@ __global__ __launch_bounds__(256) void token_gather_kernel(const char* __restric
 
 // ---------------------------------------------------------------------------- host side
 static int num_compute_units() {
-    static int cached = 0;                       // per process; devices of one machine are alike
-    if (cached == 0) {
+    // asked once per process (devices of one machine are alike); the initialisation of a local static
+    // is safe against concurrent first calls
+    static const int cached = [] {
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
             cus = 256;
-        cached = cus;
-    }
+        return cus;
+    }();
     return cached;
 }
 

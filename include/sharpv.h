@@ -17,7 +17,8 @@
  * Conventions (all entry points)
  *   - Every tensor pointer is CALLER-OWNED DEVICE MEMORY on the current HIP device unless it is
  *     marked "host".  The library never allocates, frees or keeps device memory; scratch space
- *     comes from the caller's workspace (query the size first).  Base pointers of feats / hidden /
+ *     comes from the caller's workspace (query the size first; sharpv_prune_kv_static uses a fixed
+ *     array of its own instead).  Base pointers of feats / hidden /
  *     orig / K / V / their outputs must be 16-byte aligned, the workspace 256-byte aligned.
  *   - Calls only ENQUEUE kernels on `stream` (a hipStream_t passed as void*; NULL = the null stream)
  *     and return without synchronising; they allocate nothing and record no memset, so a sequence
@@ -48,7 +49,8 @@ typedef enum {
     SHARPV_ERR_DTYPE = 3,       /* params->dtype is not a sharpv_dtype */
     SHARPV_ERR_PARAM = 4,       /* params->struct_size / mode / kv_mode / min_keep / measure invalid */
     SHARPV_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or too small */
-    SHARPV_ERR_DEVICE = 6       /* a HIP call or kernel launch failed */
+    SHARPV_ERR_DEVICE = 6,      /* a HIP call or kernel launch failed */
+    SHARPV_ERR_STATIC_LIMIT = 7 /* sharpv_prune_kv_static only: S or B beyond the built-in scratch */
 } sharpv_status;
 
 typedef enum { SHARPV_F32 = 0, SHARPV_BF16 = 1 } sharpv_dtype;
@@ -144,6 +146,37 @@ int sharpv_prune_kv(
     float* out_cos,                /* device [n_vis] cosine per visual token, or NULL */
     float* out_mean_cos,           /* device [B] mean cosine per sequence, or NULL */
     void* workspace, size_t workspace_bytes,
+    void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * sharpv_prune_kv for callers that cannot allocate or carry a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * Same arguments (without the workspace), decisions and outputs as sharpv_prune_kv.  The scratch memory
+ * of its kernels (keep mask, per-sequence flags, cosines, mask prefix) is a fixed 1.25 MiB array inside
+ * the library's code object; each GPU the library runs on holds its own copy until the process ends.
+ * The call allocates nothing and frees nothing.  Its first call on a device looks the array's address up
+ * (hipGetSymbolAddress, once per device, with that device current); make that first call outside a
+ * stream capture.
+ *
+ * Limits beyond those of sharpv_prune_kv: S <= SHARPV_STATIC_MAX_S, B <= SHARPV_STATIC_MAX_B; larger calls
+ * return SHARPV_ERR_STATIC_LIMIT and touch nothing.  All calls on one GPU share that GPU's array, which
+ * keeps the previous call's contents (the kernels overwrite every word they later read, so nothing has
+ * to be cleared): calls that overlap in time on one GPU -- other streams, other host threads -- race.
+ * Calls on one stream are ordered.
+ */
+#define SHARPV_STATIC_MAX_S 262144
+#define SHARPV_STATIC_MAX_B 256
+
+int sharpv_prune_kv_static(
+    const void* hidden, const void* orig, const void* K, const void* V,
+    int64_t kv_stride_h, int64_t kv_stride_s,
+    const int32_t* seq_offsets, const int32_t* vis_start, const int32_t* vis_offsets,
+    int B, int S, int vis_start0, int n_vis, int d, int H, int D, int layer,
+    const sharpv_params* params,   /* host */
+    int32_t* out_idx, int32_t* out_count,
+    void* K_out, void* V_out, int64_t out_stride_h,
+    float* out_cos, float* out_mean_cos,
     void* stream);
 
 /* ------------------------------------------------------------------------------------------------

@@ -2,6 +2,7 @@
 // launch sequences of sharpv_tokens.hip / sharpv_kv.hip.  Also the optional event timing.
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "sharpv_kernels.hpp"
@@ -83,6 +84,38 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// ---------------------------------------------------------------------------- scratch of sharpv_prune_kv_static
+// The intra-LLM stage's scratch (keep mask, per-sequence flags, cosines, mask prefix) for callers that may
+// not allocate: a fixed array inside the library's code object instead of a caller workspace.  Every GPU
+// the library runs on holds its own copy, at its own address, until the process ends.
+constexpr int kStaticMaxS = SHARPV_STATIC_MAX_S;     // packed positions
+constexpr int kStaticMaxB = SHARPV_STATIC_MAX_B;     // sequences
+constexpr size_t kStaticScratchBytes = (size_t)5 << 18;   // 1.25 MiB >= the workspace of the largest admitted call
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle
+// for hipGetSymbolAddress, never an address a kernel could use; the address is asked for once per
+// device (with that device current) and kept.
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SHARPV_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return SHARPV_ERR_DEVICE;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SHARPV_OK;
+}
+
 static int check_params(const sharpv_params* p) {
     if (p == nullptr) return SHARPV_ERR_NULL;
     if (p->struct_size != sizeof(sharpv_params)) return SHARPV_ERR_PARAM;
@@ -139,6 +172,7 @@ const char* sharpv_status_string(int status) {
         case SHARPV_ERR_PARAM: return "invalid parameter block";
         case SHARPV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case SHARPV_ERR_DEVICE: return "HIP call or kernel launch failed";
+        case SHARPV_ERR_STATIC_LIMIT: return "sizes beyond what the library's built-in scratch holds";
         default: return "unknown status";
     }
 }
@@ -196,7 +230,7 @@ static int prune_kv_checked(const void* hidden, const void* orig, const void* K,
                             void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos,
                             const float* rope_cos, const float* rope_sin, int rope_len, int rope_layout,
                             const int32_t* orig_row, int32_t* out_orig_row,
-                            void* workspace, size_t workspace_bytes, void* stream) {
+                            void* workspace, size_t workspace_bytes, void* stream, bool validate_only = false) {
     int rc = check_params(params);
     if (rc != SHARPV_OK) return rc;
     if (hidden == nullptr || orig == nullptr || K == nullptr || V == nullptr || K_out == nullptr ||
@@ -223,6 +257,7 @@ static int prune_kv_checked(const void* hidden, const void* orig, const void* K,
         !aligned(V_out, 16) || !aligned(out_idx, 4) || !aligned(out_count, 4))
         return SHARPV_ERR_SHAPE;
     if (K_out == K || V_out == V || K_out == V || V_out == K) return SHARPV_ERR_SHAPE;
+    if (validate_only) return SHARPV_OK;         // everything but the workspace has been checked
     if (workspace == nullptr || !aligned(workspace, 256) ||
         workspace_bytes < carve_kv_workspace(nullptr, B, S, orig_row != nullptr ? S : n_vis).bytes)
         return SHARPV_ERR_WORKSPACE;
@@ -254,6 +289,30 @@ int sharpv_prune_kv(const void* hidden, const void* orig, const void* K, const v
     return prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, vis_start, vis_offsets, B, S,
                             vis_start0, n_vis, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h,
                             out_cos, out_mean_cos, nullptr, nullptr, 0, 0, nullptr, nullptr, workspace, workspace_bytes,
+                            stream);
+}
+
+int sharpv_prune_kv_static(const void* hidden, const void* orig, const void* K, const void* V, int64_t kv_stride_h,
+                           int64_t kv_stride_s, const int32_t* seq_offsets, const int32_t* vis_start,
+                           const int32_t* vis_offsets, int B, int S, int vis_start0, int n_vis, int d, int H, int D,
+                           int layer, const sharpv_params* params, int32_t* out_idx, int32_t* out_count, void* K_out,
+                           void* V_out, int64_t out_stride_h, float* out_cos, float* out_mean_cos, void* stream) {
+    (void)layer;
+    // argument errors first (as in sharpv_prune_kv; they need no GPU), then the limits of the built-in
+    // scratch, and only then its address
+    const int rc_args = prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, vis_start,
+                                         vis_offsets, B, S, vis_start0, n_vis, d, H, D, params, out_idx, out_count,
+                                         K_out, V_out, out_stride_h, out_cos, out_mean_cos, nullptr, nullptr, 0, 0,
+                                         nullptr, nullptr, /*workspace=*/nullptr, 0, stream, /*validate_only=*/true);
+    if (rc_args != SHARPV_OK) return rc_args;
+    if (S > kStaticMaxS || B > kStaticMaxB || carve_kv_workspace(nullptr, B, S, n_vis).bytes > kStaticScratchBytes)
+        return SHARPV_ERR_STATIC_LIMIT;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != SHARPV_OK) return rc;
+    return prune_kv_checked(hidden, orig, K, V, kv_stride_h, kv_stride_s, seq_offsets, vis_start, vis_offsets, B, S,
+                            vis_start0, n_vis, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h,
+                            out_cos, out_mean_cos, nullptr, nullptr, 0, 0, nullptr, nullptr, ws, kStaticScratchBytes,
                             stream);
 }
 

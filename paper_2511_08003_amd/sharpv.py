@@ -61,6 +61,10 @@ def load() -> C.CDLL:
     L.sharpv_prune_kv.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, ip, ip, ip, C.c_int, C.c_int, C.c_int,
                                   C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64,
                                   fp, fp, vp, C.c_size_t, vp]
+    L.sharpv_prune_kv_static.restype = C.c_int
+    L.sharpv_prune_kv_static.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, ip, ip, ip, C.c_int, C.c_int, C.c_int,
+                                         C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64,
+                                         fp, fp, vp]
     L.sharpv_prune_kv_rope.restype = C.c_int
     L.sharpv_prune_kv_rope.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, ip, ip, ip, C.c_int, C.c_int, C.c_int,
                                        C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, pp, ip, ip, vp, vp, C.c_int64,
@@ -225,6 +229,20 @@ class KvPlan:
                                       self.out_count.data_ptr(), self.K_out.data_ptr(), self.V_out.data_ptr(),
                                       self.K_out.stride(0), _ptr(self.out_cos), _ptr(self.out_mean_cos),
                                       self.workspace.data_ptr(), self.workspace_bytes, _stream())
+
+    def run_static(self, hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                   vis_start0: int = 0, seq_offsets: Optional[torch.Tensor] = None,
+                   vis_start: Optional[torch.Tensor] = None, vis_offsets: Optional[torch.Tensor] = None,
+                   layer: int = 0) -> int:
+        """Enqueues `sharpv_prune_kv_static`: the same call on the library's built-in scratch (the plan's
+        workspace is not used)."""
+        return load().sharpv_prune_kv_static(hidden.data_ptr(), orig.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                             K.stride(0), K.stride(1), _ptr(seq_offsets), _ptr(vis_start),
+                                             _ptr(vis_offsets), self.B, self.S, vis_start0, self.n_vis, self.d,
+                                             self.H, self.D, layer, C.byref(self.params), self.out_idx.data_ptr(),
+                                             self.out_count.data_ptr(), self.K_out.data_ptr(), self.V_out.data_ptr(),
+                                             self.K_out.stride(0), _ptr(self.out_cos), _ptr(self.out_mean_cos),
+                                             _stream())
 
     def results(self) -> Dict[str, torch.Tensor]:
         total = int(self.out_count.sum().item())

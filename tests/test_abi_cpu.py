@@ -56,6 +56,15 @@ def test_workspace_queries(lib):
     assert lib.sharpv_prune_kv_workspace(0, 100, 10, C.byref(p)) == 0
 
 
+def _no_gpu_here():
+    """The calls below pass made-up device addresses; every one of them must be rejected on the host.
+    With a GPU in the process a regression of a check would launch kernels on those addresses, so the
+    fake-pointer cases only run where no device is visible."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("fake device addresses are only passed where no GPU could be reached")
+
+
 def _tok_call(lib, p, feats=0x1000, fo=None, B=1, n=4, f=16, d=64, idx=0x2000, cnt=0x3000, off=0x4000,
               out=0x5000, ws=0x10000, ws_bytes=1 << 30):
     # fake, well-aligned addresses: validation must return before anything is dereferenced
@@ -63,6 +72,7 @@ def _tok_call(lib, p, feats=0x1000, fo=None, B=1, n=4, f=16, d=64, idx=0x2000, c
 
 
 def test_prune_tokens_rejects_bad_arguments_on_the_host(lib):
+    _no_gpu_here()
     p = sharpv.default_params()
     assert _tok_call(lib, p, feats=None) == 1
     assert _tok_call(lib, p, idx=None) == 1
@@ -103,6 +113,7 @@ def _kv_call(lib, p, hidden=0x1000, orig=0x2000, K=0x3000, V=0x4000, sh=64 * 32,
 
 
 def test_prune_kv_rejects_bad_arguments_on_the_host(lib):
+    _no_gpu_here()
     p = sharpv.default_params()
     assert _kv_call(lib, p, hidden=None) == 1
     assert _kv_call(lib, p, Ko=None) == 1
@@ -119,6 +130,26 @@ def test_prune_kv_rejects_bad_arguments_on_the_host(lib):
     assert _kv_call(lib, q) == 4
 
 
+def test_prune_kv_static_rejects_bad_arguments_and_sizes_on_the_host(lib):
+    _no_gpu_here()
+    p = sharpv.default_params()
+
+    def call(hidden=0x1000, S=64, B=1, nv=40, so=None, vs=None, vo=None, Ko=0x7000, params=p):
+        return lib.sharpv_prune_kv_static(hidden, 0x2000, 0x3000, 0x4000, S * 32, 32, so, vs, vo, B, S, 4, nv, 64, 2, 32,
+                                          0, C.byref(params), 0x5000, 0x6000, Ko, 0x8000, S * 32, None, None, None)
+    assert call(hidden=None) == 1                            # the checks of sharpv_prune_kv come first
+    assert call(nv=80) == 2
+    assert call(Ko=0x3000) == 2
+    q = sharpv.default_params(); q.kv_mode = 3
+    assert call(params=q) == 4
+    assert call(S=262144 + 1) == 7                           # beyond the built-in scratch
+    assert call(S=1 << 20, nv=0) == 7
+    assert call(S=4096, B=257, so=0x9000, vs=0xA000, vo=0xB000) == 7
+    assert "scratch" in sharpv.status_string(7)
+    # a call that passes every check needs the scratch's device address next: no device here
+    assert call() == 6
+
+
 def _kv_rope_call(lib, p, cos=0xA000, sin=0xB000, rope_len=64, layout=0, D=32, ws_bytes=1 << 30, hidden=0x1000):
     return lib.sharpv_prune_kv_rope(hidden, 0x2000, 0x3000, 0x4000, 64 * D, D, None, None, None, 1, 64, 4, 40, 64, 2,
                                     D, 0, C.byref(p), 0x5000, 0x6000, 0x7000, 0x8000, 64 * D, None, None, cos, sin,
@@ -126,6 +157,7 @@ def _kv_rope_call(lib, p, cos=0xA000, sin=0xB000, rope_len=64, layout=0, D=32, w
 
 
 def test_prune_kv_rope_rejects_bad_arguments_on_the_host(lib):
+    _no_gpu_here()
     p = sharpv.default_params()
     assert _kv_rope_call(lib, p, cos=None) == 1
     assert _kv_rope_call(lib, p, sin=None) == 1
@@ -145,6 +177,7 @@ def _kv_carried_call(lib, p, rows=0x9000, out_rows=0xC000, n_orig=500, B=1, so=N
 
 
 def test_prune_kv_carried_rejects_bad_arguments_on_the_host(lib):
+    _no_gpu_here()
     p = sharpv.default_params()
     assert lib.sharpv_prune_kv_carried_workspace(1, 64, C.byref(p)) == lib.sharpv_prune_kv_workspace(1, 64, 64, C.byref(p))
     assert _kv_carried_call(lib, p, rows=None) == 1

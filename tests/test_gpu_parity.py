@@ -5,16 +5,21 @@ Bars: kept counts, kept-index lists, compacted features / K / V, scores I, ratio
 compared BIT-EXACTLY with the float32 canonical-order oracle (same precision, same order of
 roundings); scores and cosines are also compared with the float64 definition within 1e-3 relative
 (absolute floor 1e-4 where 2 - 2cos cancels near zero)."""
+import json
+import os
+
 import numpy as np
 import pytest
 import torch
 
+import margins
 from oracle import canon, sharpv_ref as ref
 from paper_2511_08003_amd import sharpv, workloads as wl
 
 pytestmark = pytest.mark.gpu
 
 RTOL, ATOL = 1e-3, 1e-4
+GOLD_MARGINS = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "margin_audit.json")))
 
 
 def dev(a: np.ndarray, dtype: int) -> torch.Tensor:
@@ -61,6 +66,12 @@ def check_tokens(feats, dtype, frame_offsets, ref_frames=None, **over):
     a = ref.prune_tokens(feats[:m], dtype, np.asarray(cut), **kw)
     np.testing.assert_allclose(got["I"].cpu().numpy()[:m], a["I"], rtol=RTOL, atol=ATOL)
     np.testing.assert_allclose(got["ratio"].cpu().numpy()[:m], a["ratio"], rtol=RTOL, atol=ATOL)
+    if m == n and kw.get("mode", 0) == 0:
+        # the GPU's kept counts and kept sets against the float64 definition: they may differ only where
+        # the definition's own value sits within float32 error of the decision's boundary
+        exp["audit"] = margins.audit_token_decisions(a, got["counts"].cpu().numpy(), got["idx"].cpu().numpy(),
+                                                     got["offsets"].cpu().numpy(), f)
+        exp["audit"].update(margins.token_margins(a, f))
     return exp
 
 
@@ -77,7 +88,7 @@ def run_kv(hidden, orig, K, V, dtype, lay: wl.KVLayout, ragged=None, mean_cos=Fa
     return got
 
 
-def check_kv(hidden, orig, K, V, dtype, lay, ragged=None, **over):
+def check_kv(hidden, orig, K, V, dtype, lay, ragged=None, cos64=None, **over):
     kw = {k: over[k] for k in ("M", "kv_mode") if k in over}
     got = run_kv(hidden, orig, K, V, dtype, lay, ragged=ragged, mean_cos=True, **kw)
     args = (hidden, orig, K, V, dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets)
@@ -88,8 +99,13 @@ def check_kv(hidden, orig, K, V, dtype, lay, ragged=None, **over):
     np.testing.assert_array_equal(got["mean_cos"].cpu().numpy(), exp["mean_cos"])
     np.testing.assert_array_equal(host(got["K_out"], dtype), exp["K_out"])
     np.testing.assert_array_equal(host(got["V_out"], dtype), exp["V_out"])
-    a = ref.prune_kv(hidden, orig, K, V, dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets, **kw)
-    np.testing.assert_allclose(got["cos"].cpu().numpy(), a["cos"], rtol=RTOL, atol=ATOL)
+    if cos64 is None:
+        cos64 = ref.prune_kv(hidden, orig, K, V, dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets, **kw)["cos"]
+    np.testing.assert_allclose(got["cos"].cpu().numpy(), cos64, rtol=RTOL, atol=ATOL)
+    if kw.get("kv_mode", 0) == 0:
+        # the GPU's Eq.7 decisions against the float64 cosines: only tokens within float32 error of M may differ
+        kept = margins.kept_visual_mask(got["idx"].cpu().numpy(), lay.seq_offsets, lay.vis_start, lay.vis_offsets)
+        exp["audit"] = margins.audit_kv_decisions(cos64, kw.get("M", 0.2), kept)
     return exp
 
 
@@ -111,9 +127,14 @@ def workloads():
 def test_prune_tokens_on_config(workloads, index):
     cfg, tok = workloads(index)
     print(f"config {index}: {cfg.name} frames={tok.n_total} f={cfg.f} d={cfg.d}", flush=True)
-    exp = check_tokens(tok.feats, cfg.dtype, tok.frame_offsets, ref_frames=48)
+    exp = check_tokens(tok.feats, cfg.dtype, tok.frame_offsets)          # float64 definition on every frame
     vr = exp["counts"].sum() / (tok.n_total * cfg.f)
     assert 0.02 < vr < 0.9
+    # the margin audit of this configuration is the one on record (tests/golden/margin_audit.json)
+    want = GOLD_MARGINS[str(index)]["stage1"]
+    print(f"config {index} margin audit: {exp['audit']}", flush=True)
+    assert {k: exp["audit"][k] for k in ("k_fragile", "topk_fragile", "k_differs", "sets_differ")} == \
+        {k: want[k] for k in ("k_fragile", "topk_fragile", "k_differs", "sets_differ")}
 
 
 @pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6, 7])
@@ -122,11 +143,15 @@ def test_prune_kv_on_config(workloads, index):
     lay = wl.kv_layout_for(cfg)
     orig = tok.feats.reshape(-1, cfg.d)
     orig32 = wl.storage_to_f32(tok.feats, tok.dtype).reshape(-1, cfg.d)
-    layers = cfg.kv_layers if index != 5 else (0, 9, 20)
-    for layer in layers:
-        print(f"config {index} layer {layer}: S={lay.S} n_vis={lay.n_vis}", flush=True)
-        kv = wl.kv_layer_for(cfg, tok, layer, threads=8, orig32=orig32)
-        exp = check_kv(kv["hidden"], orig, kv["K"], kv["V"], cfg.dtype, lay)
+    for layer in cfg.kv_layers:                      # every evaluated layer (all 28 of the 256-frame video)
+        kv = wl.kv_layer_for(cfg, tok, layer, threads=16, orig32=orig32)
+        cos64 = margins.cos64_rows(kv["hidden"], orig, cfg.dtype, lay.seq_offsets, lay.vis_start, lay.vis_offsets,
+                                   threads=16)
+        exp = check_kv(kv["hidden"], orig, kv["K"], kv["V"], cfg.dtype, lay, cos64=cos64)
+        print(f"config {index} layer {layer}: S={lay.S} n_vis={lay.n_vis} kept={len(exp['idx'])} "
+              f"audit={exp['audit']}", flush=True)
+        want = GOLD_MARGINS[str(index)]["kv"][str(layer)]
+        assert (exp["audit"]["near_M"], exp["audit"]["differs"]) == (want["near_M"], want["differs"])
         if layer == 0 and cfg.drift == "layer":
             assert len(exp["idx"]) == lay.S          # decoder input: nothing degraded yet
 

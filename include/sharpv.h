@@ -22,15 +22,17 @@
  *     orig / K / V / their outputs must be 16-byte aligned, the workspace 256-byte aligned.
  *   - Calls only ENQUEUE kernels on `stream` (a hipStream_t passed as void*; NULL = the null stream)
  *     and return without synchronising; they allocate nothing and record no memset, so a sequence
- *     of calls can be captured into a HIP graph and replayed (with event timing switched off).  Counts stay on the device, so output buffers are sized
- *     for the worst case (everything kept).
+ *     of calls can be captured into a HIP graph and replayed (with the event timing of sharpv_bench.h off).
+ *     Counts stay on the device, so output buffers are sized for the worst case (everything kept).
  *   - The return value is a sharpv_status.  Argument errors are found on the host before any
  *     launch and leave every output untouched; nothing throws or aborts across this boundary.
  *   - Inputs must be finite.  Scores are accumulated in float32 in a fixed order, so results do
  *     not depend on launch geometry and repeat bit for bit.
  *   - Overlapping calls that share a workspace race; calls on one stream are ordered.
  *   - The pruning calls keep no state of their own: host threads may call them at the same time, each
- *     with its own workspace and outputs.  The event-timing calls are the exception (see there).
+ *     with its own workspace and outputs.
+ *   - Measurement aids (per-kernel event timing, plain streaming copy / read) are declared apart, in
+ *     sharpv_bench.h; nothing in this header depends on them.
  */
 #ifndef SHARPV_H
 #define SHARPV_H
@@ -121,7 +123,9 @@ int sharpv_prune_tokens(
  *
  * K and V are [H, S, D] with element strides kv_stride_h (between heads) and kv_stride_s (between
  * positions), D contiguous.  K_out / V_out receive [H, S_kept, D] with head stride out_stride_h
- * (>= S*D is always enough) and position stride D; they must not overlap K / V.
+ * (>= S*D is always enough) and position stride D; the byte ranges they may be written in
+ * ([base, base + (H-1)*out_stride_h + S*D) elements) must not overlap the ranges K / V span nor each
+ * other (checked on the host: SHARPV_ERR_SHAPE).
  *
  * Limits: d a positive multiple of 8 up to 65536; D*sizeof(element) and all strides*sizeof(element)
  * multiples of 16; 1 <= B <= S < 2^31; 0 <= n_vis <= S.
@@ -242,31 +246,6 @@ int sharpv_prune_kv_carried(
     const float* rope_cos, const float* rope_sin, int rope_len, int rope_layout,   /* both NULL: K rows copied as they are */
     void* workspace, size_t workspace_bytes,
     void* stream);
-
-/* ------------------------------------------------------------------------------------------------
- * Per-kernel timing with HIP events on the launch stream (for benchmarks; off by default).
- * While enabled, every kernel launch of the two entry points is bracketed by a pair of events
- * taken from a pool of `max_launches` pairs (launches beyond the pool go untimed).
- * sharpv_timing_read synchronises on the recorded events and returns, for the kernel with the
- * given name, the number of timed launches and their summed duration in milliseconds.
- * Kernel names: "frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
- * "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read".  Not thread-safe;
- * one device.
- */
-int sharpv_timing_enable(int max_launches);     /* creates the pool; resets earlier records */
-int sharpv_timing_disable(void);                /* destroys the pool */
-int sharpv_timing_read(const char* kernel_name, int* n_launches /* host */, double* total_ms /* host */);
-
-/* ------------------------------------------------------------------------------------------------
- * Measurement aids (not part of the method): a plain streaming copy and a plain streaming read of
- * `bytes` bytes (a multiple of 16; 16-byte aligned device pointers), enqueued on `stream`.  They give
- * the practical HBM ceiling of the device next to the pruning kernels, and a copy of known size
- * against which hardware byte counters can be scaled.  sharpv_stream_read writes one 4-byte word to
- * `sink` (device) only if the data XORs to a magic value, i.e. practically never.
- * Timed under the kernel names "stream_copy" and "stream_read".
- */
-int sharpv_stream_copy(void* dst /* device */, const void* src /* device */, size_t bytes, void* stream);
-int sharpv_stream_read(const void* src /* device */, size_t bytes, uint32_t* sink /* device */, void* stream);
 
 #ifdef __cplusplus
 }

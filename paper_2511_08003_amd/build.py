@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["sharpv_api.hip", "sharpv_tokens.hip", "sharpv_kv.hip"]
+SOURCES = ["sharpv_api.hip", "sharpv_tokens.hip", "sharpv_kv.hip", "sharpv_bench.hip"]
 OUT = os.path.join(HERE, "libsharpv.so")
 
 # -ffp-contract=off: every fused multiply-add is written explicitly, nothing else may be fused.

@@ -1,86 +1,12 @@
 // C ABI of libsharpv (declared in include/sharpv.h): argument validation on the host, then the
-// launch sequences of sharpv_tokens.hip / sharpv_kv.hip.  Also the optional event timing.
+// launch sequences of sharpv_tokens.hip / sharpv_kv.hip.
 #include <string.h>
 
 #include <mutex>
-#include <vector>
 
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
-
-// ---------------------------------------------------------------------------- event timing
-namespace {
-struct TimingPool {
-    bool enabled = false;
-    std::vector<hipEvent_t> start, stop;
-    std::vector<int> kernel;        // kernel id of each used pair
-    size_t used = 0;
-    bool open = false;              // a begin without its end yet
-} g_timing;
-
-const char* const kKernelNames[kNumKernels] = {"frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan",
-                                               "token_gather", "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather",
-                                               "kv_gather_rope", "stream_copy", "stream_read"};
-}  // namespace
-
-void timing_begin(int kernel, hipStream_t st) {
-    TimingPool& t = g_timing;
-    if (!t.enabled || t.used >= t.start.size()) { t.open = false; return; }
-    t.kernel[t.used] = kernel;
-    (void)hipEventRecord(t.start[t.used], st);
-    t.open = true;
-}
-
-void timing_end(int, hipStream_t st) {
-    TimingPool& t = g_timing;
-    if (!t.enabled || !t.open) return;
-    (void)hipEventRecord(t.stop[t.used], st);
-    ++t.used;
-    t.open = false;
-}
-
-static void timing_destroy() {
-    TimingPool& t = g_timing;
-    for (hipEvent_t e : t.start) (void)hipEventDestroy(e);
-    for (hipEvent_t e : t.stop) (void)hipEventDestroy(e);
-    t.start.clear();
-    t.stop.clear();
-    t.kernel.clear();
-    t.used = 0;
-    t.open = false;
-    t.enabled = false;
-}
-
-// ---------------------------------------------------------------------------- measurement aids
-__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                          size_t n16) {
-    const size_t stride = (size_t)gridDim.x * 256 * 4;
-    for (size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x; i < n16; i += stride) {
-        uint4 v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            v[k] = load_stream(src + (i + (size_t)k * 256 < n16 ? i + (size_t)k * 256 : n16 - 1));
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (i + (size_t)k * 256 < n16) store_stream(dst + i + (size_t)k * 256, v[k]);
-    }
-}
-
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
-                                                          uint32_t* __restrict__ sink) {
-    const size_t stride = (size_t)gridDim.x * 256 * 4;
-    uint32_t acc = 0;
-    for (size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x; i < n16; i += stride) {
-        uint4 v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            v[k] = load_stream(src + (i + (size_t)k * 256 < n16 ? i + (size_t)k * 256 : i));
-#pragma unroll
-        for (int k = 0; k < 4; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
-    }
-    if (acc == 0x5ca1ab1eu) sink[0] = acc;
-}
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
@@ -256,7 +182,20 @@ static int prune_kv_checked(const void* hidden, const void* orig, const void* K,
     if (!aligned(hidden, 16) || !aligned(orig, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(K_out, 16) ||
         !aligned(V_out, 16) || !aligned(out_idx, 4) || !aligned(out_count, 4))
         return SHARPV_ERR_SHAPE;
-    if (K_out == K || V_out == V || K_out == V || V_out == K) return SHARPV_ERR_SHAPE;
+    {   // the outputs are written while the inputs are still being read by other workgroups: no byte of
+        // K_out / V_out (as far as a call that keeps everything would write) may lie inside K or V, nor
+        // may the two outputs share bytes
+        const uintptr_t in_span = (uintptr_t)(((int64_t)(H - 1) * kv_stride_h + (int64_t)(S - 1) * kv_stride_s + D) * esz);
+        const uintptr_t out_span = (uintptr_t)(((int64_t)(H - 1) * out_stride_h + (int64_t)S * D) * esz);
+        auto overlap = [](const void* a, uintptr_t na, const void* b, uintptr_t nb) {
+            const uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+            return pa < pb + nb && pb < pa + na;
+        };
+        if (overlap(K_out, out_span, K, in_span) || overlap(K_out, out_span, V, in_span) ||
+            overlap(V_out, out_span, K, in_span) || overlap(V_out, out_span, V, in_span) ||
+            overlap(K_out, out_span, V_out, out_span))
+            return SHARPV_ERR_SHAPE;
+    }
     if (validate_only) return SHARPV_OK;         // everything but the workspace has been checked
     if (workspace == nullptr || !aligned(workspace, 256) ||
         workspace_bytes < carve_kv_workspace(nullptr, B, S, orig_row != nullptr ? S : n_vis).bytes)
@@ -371,80 +310,6 @@ int sharpv_prune_kv_carried(const void* hidden, const void* orig, const int32_t*
                             n_orig, d, H, D, params, out_idx, out_count, K_out, V_out, out_stride_h, out_cos, nullptr,
                             rope_cos, rope_sin, rope_len, rope_layout, orig_row, out_orig_row, workspace,
                             workspace_bytes, stream);
-}
-
-int sharpv_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
-    if (dst == nullptr || src == nullptr) return SHARPV_ERR_NULL;
-    if (bytes == 0 || bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return SHARPV_ERR_SHAPE;
-    const size_t n16 = bytes / 16;
-    const size_t want = (n16 + 1023) / 1024;
-    const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
-    {
-        TimedLaunch tl(kStreamCopy, (hipStream_t)stream);
-        hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
-                           (uint4*)dst, n16);
-    }
-    return hipGetLastError() == hipSuccess ? SHARPV_OK : SHARPV_ERR_DEVICE;
-}
-
-int sharpv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
-    if (src == nullptr || sink == nullptr) return SHARPV_ERR_NULL;
-    if (bytes == 0 || bytes % 16 != 0 || !aligned(src, 16) || !aligned(sink, 4)) return SHARPV_ERR_SHAPE;
-    const size_t n16 = bytes / 16;
-    const size_t want = (n16 + 1023) / 1024;
-    const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
-    {
-        TimedLaunch tl(kStreamRead, (hipStream_t)stream);
-        hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, n16,
-                           sink);
-    }
-    return hipGetLastError() == hipSuccess ? SHARPV_OK : SHARPV_ERR_DEVICE;
-}
-
-int sharpv_timing_enable(int max_launches) {
-    timing_destroy();
-    if (max_launches < 1) return SHARPV_ERR_SHAPE;
-    TimingPool& t = g_timing;
-    t.start.resize((size_t)max_launches);
-    t.stop.resize((size_t)max_launches);
-    t.kernel.assign((size_t)max_launches, -1);
-    for (int i = 0; i < max_launches; ++i) {
-        if (hipEventCreate(&t.start[(size_t)i]) != hipSuccess || hipEventCreate(&t.stop[(size_t)i]) != hipSuccess) {
-            t.start.resize((size_t)i);
-            t.stop.resize((size_t)i);
-            timing_destroy();
-            return SHARPV_ERR_DEVICE;
-        }
-    }
-    t.enabled = true;
-    return SHARPV_OK;
-}
-
-int sharpv_timing_disable(void) {
-    timing_destroy();
-    return SHARPV_OK;
-}
-
-int sharpv_timing_read(const char* kernel_name, int* n_launches, double* total_ms) {
-    if (kernel_name == nullptr || n_launches == nullptr || total_ms == nullptr) return SHARPV_ERR_NULL;
-    int id = -1;
-    for (int k = 0; k < kNumKernels; ++k)
-        if (strcmp(kernel_name, kKernelNames[k]) == 0) id = k;
-    if (id < 0) return SHARPV_ERR_PARAM;
-    TimingPool& t = g_timing;
-    int cnt = 0;
-    double tot = 0.0;
-    for (size_t i = 0; i < t.used; ++i) {
-        if (t.kernel[i] != id) continue;
-        if (hipEventSynchronize(t.stop[i]) != hipSuccess) return SHARPV_ERR_DEVICE;
-        float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, t.start[i], t.stop[i]) != hipSuccess) return SHARPV_ERR_DEVICE;
-        tot += (double)ms;
-        ++cnt;
-    }
-    *n_launches = cnt;
-    *total_ms = tot;
-    return SHARPV_OK;
 }
 
 }  // extern "C"

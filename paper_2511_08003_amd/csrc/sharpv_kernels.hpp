@@ -1,5 +1,5 @@
 // Host-side plumbing shared by the translation units of libsharpv: validated argument packs,
-// workspace carving, and the optional per-kernel event timing.
+// workspace carving, and the hooks of the optional per-kernel event timing.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -121,13 +121,15 @@ inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d, int dty
 enum KernelId { kFrameSlab = 0, kFrameMean, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
                 kKvCosine, kKvMean, kKvMaskScan, kKvGather, kKvGatherRope, kStreamCopy, kStreamRead, kNumKernels };
 
-void timing_begin(int kernel, hipStream_t st);
-void timing_end(int kernel, hipStream_t st);
+// Hooks of the optional per-kernel event timing (sharpv_bench.hip).  While timing is off -- the normal
+// state -- timing_begin is one atomic load and returns -1.
+long long timing_begin(int kernel, hipStream_t st);      // reserves an event pair, records its start; -1: not timed
+void timing_end(long long ticket, hipStream_t st);
 
 struct TimedLaunch {
-    int k; hipStream_t st;
-    TimedLaunch(int kernel, hipStream_t s) : k(kernel), st(s) { timing_begin(k, st); }
-    ~TimedLaunch() { timing_end(k, st); }
+    long long ticket; hipStream_t st;
+    TimedLaunch(int kernel, hipStream_t s) : ticket(timing_begin(kernel, s)), st(s) {}
+    ~TimedLaunch() { timing_end(ticket, st); }
 };
 
 int launch_prune_tokens(const TokArgs& a);

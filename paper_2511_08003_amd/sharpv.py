@@ -127,6 +127,14 @@ def _require_gpu(*tensors: Optional[torch.Tensor]) -> None:
             raise ValueError("tensors must be contiguous and live on the GPU")
 
 
+def _same_dtype(params: "Params", **tensors: Optional[torch.Tensor]) -> None:
+    """Every storage tensor of a call must have the element type the parameter block names: the library
+    only sees pointers, so a tensor of another type would be reinterpreted silently."""
+    for name, t in tensors.items():
+        if t is not None and dtype_of(t) != params.dtype:
+            raise TypeError(f"{name} is {t.dtype} but params.dtype says {'bfloat16' if params.dtype == BF16 else 'float32'}")
+
+
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
@@ -180,6 +188,7 @@ def prune_tokens(feats: torch.Tensor, frame_offsets: Optional[torch.Tensor] = No
         raise ValueError("feats must be [n_frames, f, d]")
     if params is None:
         params = default_params(dtype_of(feats), **over)
+    _same_dtype(params, feats=feats)
     n, f, d = feats.shape
     plan = TokensPlan(n, f, d, params, device=feats.device)
     check(plan.run(feats, frame_offsets), "sharpv_prune_tokens")
@@ -273,6 +282,7 @@ def prune_kv(hidden: torch.Tensor, orig: torch.Tensor, K: torch.Tensor, V: torch
         raise ValueError("K and V must be GPU tensors [H, S, D] with equal strides and D contiguous")
     if params is None:
         params = default_params(dtype_of(hidden), **over)
+    _same_dtype(params, hidden=hidden, orig=orig, K=K, V=V)
     S, d = hidden.shape
     H, _, D = K.shape
     B = 1 if seq_offsets is None else seq_offsets.numel() - 1
@@ -339,6 +349,7 @@ def prune_kv_carried(hidden: torch.Tensor, orig: torch.Tensor, orig_row: torch.T
         raise ValueError("orig_row must be int32 [S]")
     if params is None:
         params = default_params(dtype_of(hidden), **over)
+    _same_dtype(params, hidden=hidden, orig=orig, K=K, V=V)
     S, d = hidden.shape
     H, _, D = K.shape
     B = 1 if seq_offsets is None else seq_offsets.numel() - 1

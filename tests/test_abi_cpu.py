@@ -9,7 +9,7 @@ import pytest
 from paper_2511_08003_amd import sharpv
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "sharpv.h")
+HEADERS = [os.path.join(ROOT, "include", "sharpv.h"), os.path.join(ROOT, "include", "sharpv_bench.h")]
 
 
 @pytest.fixture(scope="module")
@@ -21,7 +21,7 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(sharpv_[a-z_0-9]+)\s*\(", text)))
 
@@ -105,8 +105,8 @@ def test_prune_tokens_rejects_bad_arguments_on_the_host(lib):
                                    0x10000, 1 << 30, None) == 1
 
 
-def _kv_call(lib, p, hidden=0x1000, orig=0x2000, K=0x3000, V=0x4000, sh=64 * 32, ss=32, so=None, vs=None, vo=None,
-             B=1, S=64, v0=4, nv=40, d=64, H=2, D=32, idx=0x5000, cnt=0x6000, Ko=0x7000, Vo=0x8000, osh=64 * 32,
+def _kv_call(lib, p, hidden=0x1000, orig=0x2000, K=0x30000, V=0x40000, sh=64 * 32, ss=32, so=None, vs=None, vo=None,
+             B=1, S=64, v0=4, nv=40, d=64, H=2, D=32, idx=0x5000, cnt=0x6000, Ko=0x70000, Vo=0x80000, osh=64 * 32,
              ws=0x10000, ws_bytes=1 << 30):
     return lib.sharpv_prune_kv(hidden, orig, K, V, sh, ss, so, vs, vo, B, S, v0, nv, d, H, D, 0, C.byref(p), idx,
                                cnt, Ko, Vo, osh, None, None, ws, ws_bytes, None)
@@ -124,7 +124,14 @@ def test_prune_kv_rejects_bad_arguments_on_the_host(lib):
     assert _kv_call(lib, p, D=4) == 2                        # row not a multiple of 16 bytes
     assert _kv_call(lib, p, ss=20) == 2
     assert _kv_call(lib, p, d=12) == 2
-    assert _kv_call(lib, p, Ko=0x3000) == 2                  # output aliases input
+    assert _kv_call(lib, p, Ko=0x30000) == 2                 # output aliases input
+    # K spans 2 heads x 64 positions x 32 bf16 = 8192 bytes from 0x3000; outputs may not touch any of them
+    assert _kv_call(lib, p, K=0x30000, V=0x40000, Ko=0x30000 + 64) == 2      # in-place compaction, one row on
+    assert _kv_call(lib, p, K=0x30000, V=0x40000, Ko=0x30000 + 8192 - 16) == 2
+    assert _kv_call(lib, p, K=0x30000, V=0x40000, Ko=0x30000 - 8192 + 16) == 2
+    assert _kv_call(lib, p, K=0x30000, V=0x40000, Ko=0x50000, Vo=0x50000 + 4096) == 2    # the outputs overlap each other
+    assert _kv_call(lib, p, K=0x30000, V=0x40000, Ko=0x40000 + 4096, Vo=0x60000) == 2    # K_out inside V
+    assert _kv_call(lib, p, K=0x30000, V=0x40000, Ko=0x32000, Vo=0x42000, ws_bytes=8) == 5   # adjacent is fine
     assert _kv_call(lib, p, ws_bytes=8) == 5
     q = sharpv.default_params(); q.kv_mode = 3
     assert _kv_call(lib, q) == 4
@@ -134,12 +141,12 @@ def test_prune_kv_static_rejects_bad_arguments_and_sizes_on_the_host(lib):
     _no_gpu_here()
     p = sharpv.default_params()
 
-    def call(hidden=0x1000, S=64, B=1, nv=40, so=None, vs=None, vo=None, Ko=0x7000, params=p):
-        return lib.sharpv_prune_kv_static(hidden, 0x2000, 0x3000, 0x4000, S * 32, 32, so, vs, vo, B, S, 4, nv, 64, 2, 32,
-                                          0, C.byref(params), 0x5000, 0x6000, Ko, 0x8000, S * 32, None, None, None)
+    def call(hidden=0x1000, S=64, B=1, nv=40, so=None, vs=None, vo=None, Ko=0x7 << 32, params=p):
+        return lib.sharpv_prune_kv_static(hidden, 0x2000, 0x3 << 32, 0x4 << 32, S * 32, 32, so, vs, vo, B, S, 4, nv, 64, 2, 32,
+                                          0, C.byref(params), 0x5000, 0x6000, Ko, 0x8 << 32, S * 32, None, None, None)
     assert call(hidden=None) == 1                            # the checks of sharpv_prune_kv come first
     assert call(nv=80) == 2
-    assert call(Ko=0x3000) == 2
+    assert call(Ko=0x3 << 32) == 2
     q = sharpv.default_params(); q.kv_mode = 3
     assert call(params=q) == 4
     assert call(S=262144 + 1) == 7                           # beyond the built-in scratch
@@ -151,8 +158,8 @@ def test_prune_kv_static_rejects_bad_arguments_and_sizes_on_the_host(lib):
 
 
 def _kv_rope_call(lib, p, cos=0xA000, sin=0xB000, rope_len=64, layout=0, D=32, ws_bytes=1 << 30, hidden=0x1000):
-    return lib.sharpv_prune_kv_rope(hidden, 0x2000, 0x3000, 0x4000, 64 * D, D, None, None, None, 1, 64, 4, 40, 64, 2,
-                                    D, 0, C.byref(p), 0x5000, 0x6000, 0x7000, 0x8000, 64 * D, None, None, cos, sin,
+    return lib.sharpv_prune_kv_rope(hidden, 0x2000, 0x30000, 0x40000, 64 * D, D, None, None, None, 1, 64, 4, 40, 64, 2,
+                                    D, 0, C.byref(p), 0x5000, 0x6000, 0x70000, 0x80000, 64 * D, None, None, cos, sin,
                                     rope_len, layout, 0x10000, ws_bytes, None)
 
 
@@ -171,8 +178,8 @@ def test_prune_kv_rope_rejects_bad_arguments_on_the_host(lib):
 
 def _kv_carried_call(lib, p, rows=0x9000, out_rows=0xC000, n_orig=500, B=1, so=None, cos=None, sin=None,
                      rope_len=0, S=64, ws_bytes=1 << 30):
-    return lib.sharpv_prune_kv_carried(0x1000, 0x2000, rows, 0x3000, 0x4000, 64 * 32, 32, so, B, S, n_orig, 64, 2, 32,
-                                       0, C.byref(p), 0x5000, 0x6000, 0x7000, 0x8000, 64 * 32, out_rows, None, cos,
+    return lib.sharpv_prune_kv_carried(0x1000, 0x2000, rows, 0x30000, 0x40000, 64 * 32, 32, so, B, S, n_orig, 64, 2, 32,
+                                       0, C.byref(p), 0x5000, 0x6000, 0x70000, 0x80000, 64 * 32, out_rows, None, cos,
                                        sin, rope_len, 0, 0x10000, ws_bytes, None)
 
 

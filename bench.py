@@ -266,18 +266,29 @@ def main() -> int:
     # ------------------------------------------------------------------ per-kernel durations (events around every launch)
     launches_per_step = 6 + 5 * len(layers)
     n_ceiling = 6
-    sharpv.timing_enable(launches_per_step * args.steps + 2 * n_ceiling + 8)
+    sharpv.timing_enable(launches_per_step * args.steps + 6 * n_ceiling + 8)
     for _ in range(args.steps):
         step()
     for i in range(len(layers)):
         stage2_rope(i)
     # practical HBM ceilings of this device: plain read and plain copy of buffers of the same size
-    # class (hidden states of different layers, so nothing is served from cache)
+    # class (hidden states of different layers, so nothing is served from cache); and the floors of the
+    # pre-LLM stage's two memory-bound passes: the features read in the fused kernel's slab pattern with the
+    # arithmetic left out, and the kept rows copied with the selection already made
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
     for k in range(n_ceiling):
         sharpv.stream_read(hidden[k % len(hidden)], sink)
     for k in range(n_ceiling):
         sharpv.stream_copy(tplan.out_feats, hidden[k % len(hidden)][:Nv])
+    kept_idx = tplan.out_idx[:kept_tokens].clone()
+    for k in range(n_ceiling):
+        # between two floor measurements a layer's hidden states pass through the caches, as in a step
+        sharpv.stream_read(hidden[k % len(hidden)], sink)
+        if f <= 208:
+            sharpv.stream_read_slabs(sets[k % copies][0], sink)
+        sharpv.stream_read(hidden[(k + 1) % len(hidden)], sink)
+        if kept_tokens:
+            sharpv.stream_gather_rows(tplan.out_feats, sets[k % copies][0].view(Nv, d), kept_idx)
     torch.cuda.synchronize()
     kern = {}
     for name in sharpv.KERNEL_NAMES:
@@ -306,7 +317,8 @@ def main() -> int:
     for name, b in (("kv_cosine", bytes_cos), ("kv_gather", bytes_gather_avg), ("kv_gather_rope", bytes_gather_rope_avg),
                     ("frame_slab", Nv * row),
                     ("frame_mean", Nv * row), ("token_dots", Nv * row), ("token_gather", 2 * kept_tokens * row),
-                    ("stream_read", hid_bytes), ("stream_copy", 2 * Nv * row)):
+                    ("stream_read", hid_bytes), ("stream_copy", 2 * Nv * row), ("stream_read_slabs", Nv * row),
+                    ("stream_gather_rows", 2 * kept_tokens * row)):
         if name in kern:
             kern[name]["alg_GBps"] = round(b / (kern[name]["avg_us"] * 1e-6) / 1e9, 1)
 

@@ -29,7 +29,8 @@ struct TimingPool {
 
 const char* const kKernelNames[kNumKernels] = {"frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan",
                                                "token_gather", "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather",
-                                               "kv_gather_rope", "stream_copy", "stream_read"};
+                                               "kv_gather_rope", "stream_copy", "stream_read", "stream_read_slabs",
+                                               "stream_gather_rows"};
 }  // namespace
 
 long long timing_begin(int kernel, hipStream_t st) {
@@ -97,6 +98,86 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
     if (acc == 0x5ca1ab1eu) sink[0] = acc;
 }
 
+
+// The pre-LLM stage's access pattern with the arithmetic taken out: as many workgroups as compute units,
+// each walking a run of consecutive (256-column slab, frame) pairs, 512 threads = 16 row groups x 32 lanes,
+// every thread reading 16 bytes of rows g, g+16, ... of the frame slab, one frame slab of loads in flight
+// while the one before it is consumed.  What this takes is the floor of any kernel that reads the features
+// slab by slab, run by run.
+constexpr int kPatThreads = 512;
+constexpr int kPatRows = 13;        // rows per thread: frames of up to 208 tokens
+
+__global__ __launch_bounds__(kPatThreads) void stream_read_slabs_kernel(const char* __restrict__ feats, int n, int f,
+                                                                        int row_bytes, int nslabs, int run_len,
+                                                                        int run_extra, uint32_t* __restrict__ sink) {
+    const int l = threadIdx.x & 31, g = threadIdx.x >> 5;
+    const int units = row_bytes / 16;
+    const size_t frame_bytes = (size_t)f * row_bytes;
+    uint32_t off[kPatRows];
+    uint32_t acc = 0;
+    const int w = blockIdx.x;
+    long long u = (long long)w * run_len + (w < run_extra ? w : run_extra);
+    const long long u_end = u + run_len + (w < run_extra ? 1 : 0);
+    while (u < u_end) {
+        const int slab = (int)(u / n);
+        const int t0 = (int)(u - (long long)slab * n);
+        const int t1 = (long long)t0 + (u_end - u) < n ? t0 + (int)(u_end - u) : n;
+        const int c = slab * 32 + l;
+        const uint32_t chunk_off = (uint32_t)((c < units ? c : units - 1) * 16);
+#pragma unroll
+        for (int k = 0; k < kPatRows; ++k) {
+            const int i = g + 16 * k;
+            off[k] = (uint32_t)(i < f ? i : f - 1) * (uint32_t)row_bytes + chunk_off;
+        }
+        // frames t0 .. t1 (the frame after the run included, as the real kernel reads it for x.x_prev)
+        const int last = t1 < n ? t1 : n - 1;
+        uint4 a[kPatRows], b[kPatRows];
+        const char* base = feats + (size_t)t0 * frame_bytes;
+#pragma unroll
+        for (int k = 0; k < kPatRows; ++k) a[k] = load_stream(reinterpret_cast<const uint4*>(base + off[k]));
+        for (int t = t0; t < last; t += 2) {
+            const char* nb = feats + (size_t)(t + 1) * frame_bytes;
+#pragma unroll
+            for (int k = 0; k < kPatRows; ++k) b[k] = load_stream(reinterpret_cast<const uint4*>(nb + off[k]));
+#pragma unroll
+            for (int k = 0; k < kPatRows; ++k) acc ^= a[k].x ^ a[k].y ^ a[k].z ^ a[k].w;
+            const char* nb2 = feats + (size_t)(t + 2 <= last ? t + 2 : last) * frame_bytes;
+#pragma unroll
+            for (int k = 0; k < kPatRows; ++k) a[k] = load_stream(reinterpret_cast<const uint4*>(nb2 + off[k]));
+#pragma unroll
+            for (int k = 0; k < kPatRows; ++k) acc ^= b[k].x ^ b[k].y ^ b[k].z ^ b[k].w;
+        }
+#pragma unroll
+        for (int k = 0; k < kPatRows; ++k) acc ^= a[k].x ^ a[k].y ^ a[k].z ^ a[k].w;
+        u += t1 - t0;
+    }
+    if (acc == 0x5ca1ab1eu) sink[0] = acc;
+}
+
+// Indexed row copy: dst row j = src row idx[j], one wavefront per row, 16-byte units, eight in flight per
+// lane.  The floor of a compaction whose indices are already known.
+__global__ __launch_bounds__(256) void stream_gather_rows_kernel(const char* __restrict__ src, int row_bytes,
+                                                                 const int32_t* __restrict__ idx, int n_idx,
+                                                                 char* __restrict__ dst) {
+    const int lane = threadIdx.x & 63;
+    const int units = row_bytes / 16;
+    for (int j = blockIdx.x * 4 + (threadIdx.x >> 6); j < n_idx; j += gridDim.x * 4) {
+        const uint4* s = reinterpret_cast<const uint4*>(src + (size_t)idx[j] * row_bytes);
+        uint4* d = reinterpret_cast<uint4*>(dst + (size_t)j * row_bytes);
+        for (int u0 = lane; u0 < units; u0 += 64 * 8) {
+            uint4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int u = u0 + 64 * k;
+                v[k] = load_stream(s + (u < units ? u : units - 1));
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (u0 + 64 * k < units) store_stream(d + u0 + 64 * k, v[k]);
+        }
+    }
+}
+
 static bool aligned16(const void* p) { return ((uintptr_t)p % 16) == 0; }
 
 }  // namespace sharpv
@@ -129,6 +210,41 @@ int sharpv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stre
         TimedLaunch tl(kStreamRead, (hipStream_t)stream);
         hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, n16,
                            sink);
+    }
+    return hipGetLastError() == hipSuccess ? SHARPV_OK : SHARPV_ERR_DEVICE;
+}
+
+int sharpv_stream_read_slabs(const void* feats, int n_frames, int f, int d, int elem_bytes, uint32_t* sink, void* stream) {
+    if (feats == nullptr || sink == nullptr) return SHARPV_ERR_NULL;
+    if (n_frames < 1 || f < 1 || f > 16 * kPatRows || d < 8 || (elem_bytes != 2 && elem_bytes != 4) ||
+        ((long long)d * elem_bytes) % 16 != 0 || !aligned16(feats) || ((uintptr_t)sink % 4) != 0)
+        return SHARPV_ERR_SHAPE;
+    const int row_bytes = d * elem_bytes;
+    const int nslabs = (row_bytes + 511) / 512;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return SHARPV_ERR_DEVICE;
+    const long long pairs = (long long)nslabs * n_frames;
+    const int wgs = pairs < cus ? (int)pairs : cus;
+    {
+        TimedLaunch tl(kStreamReadSlabs, (hipStream_t)stream);
+        hipLaunchKernelGGL(stream_read_slabs_kernel, dim3(wgs), dim3(kPatThreads), 0, (hipStream_t)stream,
+                           (const char*)feats, n_frames, f, row_bytes, nslabs, (int)(pairs / wgs), (int)(pairs % wgs), sink);
+    }
+    return hipGetLastError() == hipSuccess ? SHARPV_OK : SHARPV_ERR_DEVICE;
+}
+
+int sharpv_stream_gather_rows(void* dst, const void* src, int row_bytes, const int32_t* idx, int n_idx, void* stream) {
+    if (dst == nullptr || src == nullptr || idx == nullptr) return SHARPV_ERR_NULL;
+    if (row_bytes < 16 || row_bytes % 16 != 0 || n_idx < 1 || !aligned16(dst) || !aligned16(src) ||
+        ((uintptr_t)idx % 4) != 0)
+        return SHARPV_ERR_SHAPE;
+    const int want = (n_idx + 3) / 4;
+    {
+        TimedLaunch tl(kStreamGatherRows, (hipStream_t)stream);
+        hipLaunchKernelGGL(stream_gather_rows_kernel, dim3(want < 2048 ? want : 2048), dim3(256), 0, (hipStream_t)stream,
+                           (const char*)src, row_bytes, idx, n_idx, (char*)dst);
     }
     return hipGetLastError() == hipSuccess ? SHARPV_OK : SHARPV_ERR_DEVICE;
 }

@@ -119,7 +119,8 @@ inline TokWorkspace carve_tok_workspace(void* base, int n, int f, int d, int dty
 
 // ---------------------------------------------------------------------------- event timing
 enum KernelId { kFrameSlab = 0, kFrameMean, kTokenDots, kFrameSelect, kCountScan, kTokenGather,
-                kKvCosine, kKvMean, kKvMaskScan, kKvGather, kKvGatherRope, kStreamCopy, kStreamRead, kNumKernels };
+                kKvCosine, kKvMean, kKvMaskScan, kKvGather, kKvGatherRope, kStreamCopy, kStreamRead, kStreamReadSlabs,
+                kStreamGatherRows, kNumKernels };
 
 // Hooks of the optional per-kernel event timing (sharpv_bench.hip).  While timing is off -- the normal
 // state -- timing_begin is one atomic load and returns -1.

@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libsharpv.so")
 F32, BF16 = 0, 1
 OK = 0
 KERNEL_NAMES = ("frame_slab", "frame_mean", "token_dots", "frame_select", "count_scan", "token_gather",
-                "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read")
+                "kv_cosine", "kv_mean", "kv_mask_scan", "kv_gather", "kv_gather_rope", "stream_copy", "stream_read",
+                "stream_read_slabs", "stream_gather_rows")
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
 DISSIM_EQ1, ONE_MINUS_COS = 0, 1
 
@@ -79,6 +80,10 @@ def load() -> C.CDLL:
     L.sharpv_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.sharpv_stream_read.restype = C.c_int
     L.sharpv_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+    L.sharpv_stream_read_slabs.restype = C.c_int
+    L.sharpv_stream_read_slabs.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp]
+    L.sharpv_stream_gather_rows.restype = C.c_int
+    L.sharpv_stream_gather_rows.argtypes = [vp, vp, C.c_int, ip, C.c_int, vp]
     L.sharpv_timing_enable.restype = C.c_int
     L.sharpv_timing_enable.argtypes = [C.c_int]
     L.sharpv_timing_disable.restype = C.c_int
@@ -374,6 +379,26 @@ def stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
     _require_gpu(src, sink)
     check(load().sharpv_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream()),
           "sharpv_stream_read")
+
+
+def stream_read_slabs(feats: torch.Tensor, sink: torch.Tensor) -> None:
+    """Reads feats [n, f, d] in the fused statistics kernel's access pattern (f <= 208), arithmetic left out."""
+    _require_gpu(feats, sink)
+    n, f, d = feats.shape
+    check(load().sharpv_stream_read_slabs(feats.data_ptr(), n, f, d, feats.element_size(), sink.data_ptr(), _stream()),
+          "sharpv_stream_read_slabs")
+
+
+def stream_gather_rows(dst: torch.Tensor, src: torch.Tensor, idx: torch.Tensor) -> None:
+    """dst[j] = src[idx[j]] for 2-D contiguous GPU tensors of equal row size and an int32 index tensor."""
+    _require_gpu(dst, src, idx)
+    if idx.dtype != torch.int32 or src.dim() != 2 or dst.dim() != 2 or dst.shape[1] != src.shape[1] \
+            or dst.dtype != src.dtype or dst.shape[0] < idx.numel():
+        raise ValueError("stream_gather_rows: dst [>= len(idx), d] and src [rows, d] of one dtype, idx int32")
+    if idx.numel() and (int(idx.min()) < 0 or int(idx.max()) >= src.shape[0]):
+        raise ValueError("stream_gather_rows: an index points outside src")
+    check(load().sharpv_stream_gather_rows(dst.data_ptr(), src.data_ptr(), src.shape[1] * src.element_size(),
+                                           idx.data_ptr(), idx.numel(), _stream()), "sharpv_stream_gather_rows")
 
 
 # ----------------------------------------------------------------------------- event timing

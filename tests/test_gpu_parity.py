@@ -602,6 +602,31 @@ def test_stream_copy_and_read(nbytes):
     assert L.sharpv_stream_read(None, 16, sink.data_ptr(), None) == 1
 
 
+def test_floor_aids_read_in_bounds_and_copy_the_indexed_rows():
+    """The two floor aids of the pre-LLM stage: the slab-pattern read leaves no trace for any shape the fused
+    kernel takes, the indexed row copy equals torch's index_select."""
+    sink = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+    for n, f, d, dt in ((1, 196, 3584, torch.bfloat16), (7, 1, 64, torch.bfloat16), (40, 208, 520, torch.bfloat16),
+                        (300, 17, 256, torch.bfloat16), (5, 144, 1152, torch.float32)):
+        x = torch.randn((n, f, d), device="cuda").to(dt)
+        sharpv.stream_read_slabs(x, sink)
+    torch.cuda.synchronize()
+    assert int(sink[0]) == -5
+    L = sharpv.load()
+    assert L.sharpv_stream_read_slabs(x.data_ptr(), 5, 209, 1152, 4, sink.data_ptr(), None) == 2    # taller than the pattern covers
+    g = torch.Generator(device="cuda"); g.manual_seed(77)
+    for rows, d, k in ((50176, 3584, 7633), (10, 8, 1), (999, 520, 999)):
+        src = torch.randn((rows, d), device="cuda", generator=g).to(torch.bfloat16)
+        idx = torch.sort(torch.randperm(rows, device="cuda", generator=g)[:k])[0].to(torch.int32)
+        dst = torch.full((k + 1, d), 7.0, dtype=torch.bfloat16, device="cuda")
+        sharpv.stream_gather_rows(dst, src, idx)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:k], src[idx.long()])
+        assert torch.all(dst[k] == 7.0)
+    with pytest.raises(ValueError):
+        sharpv.stream_gather_rows(dst, src, torch.tensor([rows], dtype=torch.int32, device="cuda"))
+
+
 def test_event_timing_counts_launches():
     tok = small_video(801, 4, 64, 512, wl.BF16)
     x = dev(tok.feats, wl.BF16)

@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=5, help="workload 1..7 (5 = the 256-frame video; 6, 7 = other model shapes)")
+    ap.add_argument("--config", type=int, default=5, help="workload 1..8 (5 = the 256-frame video; 6, 7 = other model shapes; 8 = tall frames)")
     ap.add_argument("--layers", type=int, default=0, help="KV layers per step (0 = all layers of the config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold-mb", type=int, default=768,

@@ -10,11 +10,13 @@
 //                 mean, the slab's share of x.x and x.x_prev per row, and the share of x.mean of the frame
 //                 before.  The per-slab shares are summed in ascending slab order by frame_select.
 //   frame_mean    (other shapes) workgroup = (frame, 256-column slab), 32 row classes x 32 lanes: row i goes to
-//                 class i % 32, each class adds its rows in ascending order, the 32 classes are
-//                 reduced by a halving tree in LDS, divided by f.  Eq.2's average representation.
-//   token_dots    one wavefront per token row: x.x, x.mean_t and x.x_prev in the fixed order of
-//                 sharpv_device.hpp (the row, its predecessor in the previous frame and the frame
-//                 mean are streamed with 16-byte loads).
+//                 class i % 32, each class adds its rows in ascending order (eight streamed loads issued
+//                 before their sums), the 32 classes are reduced by a halving tree in LDS, divided by f.
+//                 Eq.2's average representation.
+//   token_dots    one wavefront per (token slot, run of frames): x.x, x.mean_t and x.x_prev in the fixed
+//                 order of sharpv_device.hpp.  The slot's row of frame t stays in registers as x_prev of
+//                 frame t+1 while the row of frame t+1 streams in, the frame mean is staged in LDS, so
+//                 this pass reads the features once more and no more than that.
 //   frame_select  one workgroup per frame: Eq.1-4 from the stored inner products, Eq.5/6 retention ratio
 //                 and kept count, rank of every token by counting 64-bit keys (score descending, index
 //                 ascending) staged in LDS, and the frame's kept rows in ascending order.
@@ -26,6 +28,8 @@
 #include "sharpv_kernels.hpp"
 
 namespace sharpv {
+
+static int num_compute_units();
 
 // ---------------------------------------------------------------------------- frame mean (Eq.2)
 template <typename T>
@@ -42,12 +46,26 @@ __global__ __launch_bounds__(1024) void frame_mean_kernel(const T* __restrict__ 
 #pragma unroll
     for (int k = 0; k < 8; ++k) p[k] = 0.0f;
     if (live) {
+        // rows g, g+32, ... in ascending order, eight loads issued before their sums (clamped row index:
+        // no load under a predicate)
         const T* col = feats + (size_t)t * f * d + (size_t)c * kChunk;
-        for (int i = g; i < f; i += 32) {
-            float v[8];
-            unpack(load_raw<T>(col + (size_t)i * d), v);
+        const int mine = f > g ? (f - g + 31) / 32 : 0;
+        for (int j0 = 0; j0 < mine; j0 += 8) {
+            RawChunk<T> r[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) p[k] = p[k] + v[k];
+            for (int j = 0; j < 8; ++j) {
+                const int i = g + 32 * (j0 + j);
+                r[j] = load_raw_stream<T>(col + (size_t)(i < f ? i : f - 1) * d);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (j0 + j < mine) {
+                    float v[8];
+                    unpack(r[j], v);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) p[k] = p[k] + v[k];
+                }
+            }
         }
     }
 #pragma unroll
@@ -398,32 +416,36 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
 }
 
 // ---------------------------------------------------------------------------- per-token inner products
+// One token row as a wavefront holds it: chunk c = 64*q + lane in sweep q.  NS = number of sweeps
+// (d <= 512*NS); FULL = every lane of every sweep holds a chunk (d == 512*NS).
+template <typename T, int NS> struct RowRegs { RawChunk<T> r[NS]; };
+
+template <typename T, int NS, bool FULL, bool STREAM>
+__device__ __forceinline__ void load_row(const T* __restrict__ row, int nchunks, int lane, RowRegs<T, NS>& out) {
+#pragma unroll
+    for (int q = 0; q < NS; ++q) {
+        const int c = q * 64 + lane;
+        // lanes past the end of the row reload its last chunk (no load under a predicate); they are
+        // masked out of the sums
+        const T* p = row + (size_t)(FULL || c < nchunks ? c : nchunks - 1) * kChunk;
+        out.r[q] = STREAM ? load_raw_stream<T>(p) : load_raw<T>(p);
+    }
+}
+
+// Any d: sweeps in a loop, straight from memory (rows wider than the unrolled sweeps cover).
 template <typename T>
-__global__ __launch_bounds__(256) void token_dots_kernel(const T* __restrict__ feats, const float* __restrict__ mean,
-                                                         int n_rows, int f, int d,
-                                                         float* __restrict__ aa, float* __restrict__ am,
-                                                         float* __restrict__ ab) {
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= n_rows) return;
-    const int t = row / f;
-    const bool has_prev = t > 0;
-    const int nchunks = d / kChunk;
-    const T* x = feats + (size_t)row * d;
-    const T* xp = has_prev ? x - (size_t)f * d : x;
-    const float* m = mean + (size_t)t * d;
-    float s_aa = 0.0f, s_am = 0.0f, s_ab = 0.0f;
+__device__ __forceinline__ void row_dots_loop(const T* __restrict__ x, const T* __restrict__ xp,
+                                              const float* __restrict__ m, int nchunks, int lane,
+                                              float* s_aa, float* s_am, float* s_ab) {
+    float aa = 0.0f, am = 0.0f, ab = 0.0f;
     for (int c0 = 0; c0 < nchunks; c0 += 64) {
         const int c = c0 + lane;
         float paa = 0.0f, pam = 0.0f, pab = 0.0f;
         if (c < nchunks) {
-            const RawChunk<T> rx = load_raw<T>(x + (size_t)c * kChunk);
-            const RawChunk<T> rp = load_raw<T>(xp + (size_t)c * kChunk);
-            const RawChunk<float> rm = load_raw<float>(m + (size_t)c * kChunk);
             float a[8], b[8], mm[8];
-            unpack(rx, a);
-            unpack(rp, b);
-            unpack(rm, mm);
+            unpack(load_raw<T>(x + (size_t)c * kChunk), a);
+            unpack(load_raw<T>(xp + (size_t)c * kChunk), b);
+            unpack(load_raw<float>(m + (size_t)c * kChunk), mm);
             paa = chain8(a, a);
             pam = chain8(a, mm);
             pab = chain8(a, b);
@@ -432,15 +454,177 @@ __global__ __launch_bounds__(256) void token_dots_kernel(const T* __restrict__ f
         pam = tree32(pam);
         pab = tree32(pab);
         const bool odd = c0 + kBlockChunks < nchunks;
-        s_aa = add_blocks(s_aa, paa, odd);
-        s_am = add_blocks(s_am, pam, odd);
-        s_ab = add_blocks(s_ab, pab, odd);
+        aa = add_blocks(aa, paa, odd);
+        am = add_blocks(am, pam, odd);
+        ab = add_blocks(ab, pab, odd);
     }
+    *s_aa = aa; *s_am = am; *s_ab = ab;
+}
+
+// One wavefront per (token slot, run of consecutive frames), four slots per workgroup, all four on the same
+// run.  The wavefront walks its slot through the frames of the run with two row buffers in registers: the
+// row of frame t and the row of frame t-1; sweep by sweep, as soon as a chunk of the older row has been
+// widened its registers receive the same chunk of frame t+1, so a whole row of loads is in flight per
+// wavefront while it works, and every feature is read once (plus one row per run, the predecessor of the
+// run's first frame).  The feature rows are streamed (non-temporal).  The frame mean, which the four slots
+// share, is staged in LDS one frame ahead (two planes of 16-byte pieces, so that a wavefront's reads meet
+// no bank twice).
+template <typename T, int NS, bool FULL>
+__global__ __launch_bounds__(256) void token_dots_kernel(const T* __restrict__ feats, const float* __restrict__ mean,
+                                                         int n, int f, int d, int run_len, int slot_blocks,
+                                                         float* __restrict__ aa, float* __restrict__ am,
+                                                         float* __restrict__ ab) {
+    constexpr int kPieces = NS * 64;             // chunks a row can have at most
+    __shared__ float4 smean[2][2][kPieces];      // [frame parity][low / high half of a chunk][chunk]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int ib = blockIdx.x % slot_blocks;
+    const int run = blockIdx.x / slot_blocks;
+    const int t0 = run * run_len;
+    if (t0 >= n) return;                         // whole workgroup
+    const int t1 = t0 + run_len < n ? t0 + run_len : n;
+    const int slot_i = ib * 4 + (tid >> 6);
+    const bool active = slot_i < f;              // a wavefront past the last slot still takes part in staging and barriers
+    const int i = active ? slot_i : f - 1;
+    const int nchunks = d / kChunk;
+    const size_t frame_elems = (size_t)f * d;
+    const T* const slot = feats + (size_t)i * d;                       // row i of frame 0
+
+    // mean row of frame t -> LDS buffer `par`: float4 piece v of the row is half v % 2 of chunk v / 2
+    constexpr int kStage = (2 * kPieces + 255) / 256;   // at most 4: 16-byte pieces of a mean row per thread
+    static_assert(kStage <= 4, "unrolled sweeps cover rows of up to 4096 elements");
+
+    // One frame: sums of row `cur` (frame t) against row `prev` (frame t-1) and the staged mean of frame
+    // t; the registers of `prev` are refilled with the row of frame t+1.
+    auto step = [&](RowRegs<T, NS>& prev, const RowRegs<T, NS>& cur, const int t) {
+        const int tn = t + 1 < n ? t + 1 : n - 1;                      // clamped: always a valid load
+        // (named registers, not an array: the stores further down sit under conditions, and an array would be
+        // indexed in memory)
+        const float4* mrow = reinterpret_cast<const float4*>(mean + (size_t)tn * d);
+        const int last_piece = 2 * nchunks - 1;
+        auto piece = [&](int k) { const int v = tid + 256 * k; return mrow[v < last_piece ? v : last_piece]; };
+        float4 st0 = piece(0), st1, st2, st3;
+        if constexpr (kStage > 1) st1 = piece(1);
+        if constexpr (kStage > 2) st2 = piece(2);
+        if constexpr (kStage > 3) st3 = piece(3);
+        const T* const next_row = slot + (size_t)tn * frame_elems;
+        const int par = t & 1;
+        float s_aa = 0.0f, s_am = 0.0f, s_ab = 0.0f;
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            const int c = q * 64 + lane;
+            const bool have = FULL || c < nchunks;
+            const int cc = have ? c : nchunks - 1;
+            float a[8], b[8], mm[8];
+            unpack(cur.r[q], a);
+            unpack(prev.r[q], b);
+            prev.r[q] = load_raw_stream<T>(next_row + (size_t)cc * kChunk);
+            const float4 lo = smean[par][0][cc], hi = smean[par][1][cc];
+            mm[0] = lo.x; mm[1] = lo.y; mm[2] = lo.z; mm[3] = lo.w;
+            mm[4] = hi.x; mm[5] = hi.y; mm[6] = hi.z; mm[7] = hi.w;
+            const float vaa = have ? chain8(a, a) : 0.0f;
+            const float vam = have ? chain8(a, mm) : 0.0f;
+            const float vab = have ? chain8(a, b) : 0.0f;
+            const float pair = tree32_pair(vaa, vam);                  // rows 0,2: x.x   rows 1,3: x.mean
+            const float single = tree32(vab);
+            const bool odd = FULL || (q * 64 + kBlockChunks < nchunks); // does the sweep's second block exist
+            s_aa = s_aa + lane_value(pair, 0);
+            s_am = s_am + lane_value(pair, 16);
+            s_ab = s_ab + lane_value(single, 0);
+            if (odd) {
+                s_aa = s_aa + lane_value(pair, 32);
+                s_am = s_am + lane_value(pair, 48);
+                s_ab = s_ab + lane_value(single, 32);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // one sweep at a time: keeps the widened copies of one chunk alive, not of all
+        }
+        if (lane == 0 && active) {
+            const size_t row = (size_t)t * f + i;
+            aa[row] = s_aa;
+            am[row] = s_am;
+            ab[row] = t > 0 ? s_ab : 0.0f;
+        }
+        // nobody reads the other buffer any more: its frame ended at the last barrier
+        auto put = [&](int k, const float4& v4) {
+            const int v = tid + 256 * k;
+            if (v <= last_piece) smean[par ^ 1][v & 1][v >> 1] = v4;
+        };
+        put(0, st0);
+        if constexpr (kStage > 1) put(1, st1);
+        if constexpr (kStage > 2) put(2, st2);
+        if constexpr (kStage > 3) put(3, st3);
+        __syncthreads();
+    };
+
+    RowRegs<T, NS> A, B;
+    load_row<T, NS, FULL, true>(slot + (size_t)(t0 > 0 ? t0 - 1 : 0) * frame_elems, nchunks, lane, A);
+    load_row<T, NS, FULL, true>(slot + (size_t)t0 * frame_elems, nchunks, lane, B);
+    {
+        const float4* mrow = reinterpret_cast<const float4*>(mean + (size_t)t0 * d);
+        for (int v = tid; v < 2 * nchunks; v += 256) smean[t0 & 1][v & 1][v >> 1] = mrow[v];
+    }
+    __syncthreads();
+    int t = t0;
+    for (; t + 1 < t1; t += 2) {
+        step(A, B, t);                           // prev = A, cur = B; A receives frame t+1
+        step(B, A, t + 1);
+    }
+    if (t < t1) step(A, B, t);
+}
+
+// Rows wider than the unrolled sweeps cover: one wavefront per row, straight from memory.
+template <typename T>
+__global__ __launch_bounds__(256) void token_dots_wide_kernel(const T* __restrict__ feats, const float* __restrict__ mean,
+                                                              int n_rows, int f, int d,
+                                                              float* __restrict__ aa, float* __restrict__ am,
+                                                              float* __restrict__ ab) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const int t = row / f;
+    const T* x = feats + (size_t)row * d;
+    const T* xp = t > 0 ? x - (size_t)f * d : x;
+    float s_aa, s_am, s_ab;
+    row_dots_loop<T>(x, xp, mean + (size_t)t * d, d / kChunk, lane, &s_aa, &s_am, &s_ab);
     if (lane == 0) {
         aa[row] = s_aa;
         am[row] = s_am;
-        ab[row] = has_prev ? s_ab : 0.0f;
+        ab[row] = t > 0 ? s_ab : 0.0f;
     }
+}
+
+template <typename T>
+static void launch_token_dots(const TokArgs& a, const TokWorkspace& ws) {
+    const int nchunks = a.d / kChunk;
+    const int ns = (nchunks + 63) / 64;
+    const bool full = nchunks == ns * 64;
+    const int slot_blocks = (a.f + 3) / 4;
+    // enough wavefronts to fill the chip (about 16 per compute unit), runs as long as that allows
+    const long long want_waves = 16ll * num_compute_units();
+    long long runs = (want_waves + a.f - 1) / a.f;
+    runs = runs < 1 ? 1 : (runs > a.n ? a.n : runs);
+    const int run_len = (int)((a.n + runs - 1) / runs);
+    const int n_runs = (a.n + run_len - 1) / run_len;
+    const dim3 grid((unsigned)((long long)slot_blocks * n_runs)), block(256);
+#define SHARPV_DOTS_CASE(NS_)                                                                                       \
+    case NS_:                                                                                                       \
+        if (full)                                                                                                   \
+            hipLaunchKernelGGL((token_dots_kernel<T, NS_, true>), grid, block, 0, a.stream, (const T*)a.feats,      \
+                               (const float*)ws.mean, a.n, a.f, a.d, run_len, slot_blocks, ws.aa, ws.am, ws.ab);    \
+        else                                                                                                        \
+            hipLaunchKernelGGL((token_dots_kernel<T, NS_, false>), grid, block, 0, a.stream, (const T*)a.feats,     \
+                               (const float*)ws.mean, a.n, a.f, a.d, run_len, slot_blocks, ws.aa, ws.am, ws.ab);    \
+        break;
+    // float32 rows take twice the registers per sweep: four sweeps (d <= 2048) unrolled, wider rows loop
+    switch (ns <= (sizeof(T) == 2 ? 8 : 4) ? ns : 0) {
+        SHARPV_DOTS_CASE(1) SHARPV_DOTS_CASE(2) SHARPV_DOTS_CASE(3) SHARPV_DOTS_CASE(4)
+        SHARPV_DOTS_CASE(5) SHARPV_DOTS_CASE(6) SHARPV_DOTS_CASE(7) SHARPV_DOTS_CASE(8)
+        default:
+            hipLaunchKernelGGL((token_dots_wide_kernel<T>), dim3((unsigned)(((long long)a.n * a.f + 3) / 4)), block, 0,
+                               a.stream, (const T*)a.feats, (const float*)ws.mean, a.n * a.f, a.f, a.d, ws.aa, ws.am,
+                               ws.ab);
+    }
+#undef SHARPV_DOTS_CASE
 }
 
 // ---------------------------------------------------------------------------- scores, ratio, top-k
@@ -778,12 +962,8 @@ int launch_prune_tokens(const TokArgs& a) {
         }
         if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
         TimedLaunch tl(kTokenDots, st);
-        if (a.dtype == SHARPV_BF16)
-            hipLaunchKernelGGL(token_dots_kernel<bf16_t>, dim3((n_rows + 3) / 4), dim3(256), 0, st,
-                               (const bf16_t*)a.feats, (const float*)ws.mean, n_rows, a.f, a.d, ws.aa, ws.am, ws.ab);
-        else
-            hipLaunchKernelGGL(token_dots_kernel<float>, dim3((n_rows + 3) / 4), dim3(256), 0, st,
-                               (const float*)a.feats, (const float*)ws.mean, n_rows, a.f, a.d, ws.aa, ws.am, ws.ab);
+        if (a.dtype == SHARPV_BF16) launch_token_dots<bf16_t>(a, ws);
+        else launch_token_dots<float>(a, ws);
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
 

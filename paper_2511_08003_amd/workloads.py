@@ -267,8 +267,8 @@ def _const_rho(n: int, rho: float) -> np.ndarray:
 
 
 def config(index: int, frames_scale: float = 1.0) -> Config:
-    """The five benchmark workloads (index 1..5) and the two other model shapes of the paper's
-    Table 2 (6, 7). `frames_scale` < 1 shrinks frame counts for quick checks; 1.0 gives the
+    """The five benchmark workloads (index 1..5), the two other model shapes of the paper's
+    Table 2 (6, 7) and a tall-frame shape (8). `frames_scale` < 1 shrinks frame counts for quick checks; 1.0 gives the
     stated sizes."""
     def nf(n: int) -> int:
         return max(2, int(round(n * frames_scale)))
@@ -316,7 +316,12 @@ def config(index: int, frames_scale: float = 1.0) -> Config:
         n = nf(32)
         v = VideoSpec(n=n, rho=_const_rho(n, 0.95), cuts=tuple(range(8, n, 8)), slot_sigma=0.5, seed=seed)
         return Config("c7_llavaov05b_32f_d896_bf16", BF16, 196, 896, [v], 32, 96, 2, 64, 24, (12,), "layer", seed)
-    raise ValueError("config index must be 1..7")
+    if index == 8:      # tall frames: 87 frames x 576 tokens (a 24 x 24 grid per frame), d=3584 bf16 -- the volume of
+                        # workload 5 in frames too tall for the register-resident statistics kernel
+        n = nf(87)
+        v = VideoSpec(n=n, rho=_const_rho(n, 0.95), cuts=tuple(range(8, n, 8)), seed=seed)
+        return Config("c8_tall_87f_576t_d3584_bf16", BF16, 576, 3584, [v], 64, 192, 4, 128, 28, (14,), "layer", seed)
+    raise ValueError("config index must be 1..8")
 
 
 def tokens_for(cfg: Config, threads: int = 8) -> TokenWorkload:

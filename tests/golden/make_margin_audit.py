@@ -1,11 +1,11 @@
-"""Writes tests/golden/margin_audit.json: for each of the five configurations (and the two other model
+"""Writes tests/golden/margin_audit.json: for each of the five configurations (and the three other
 shapes), how many decisions of the float64 definition sit within float32 error of their boundary
 (kept count k_t, top-k set, cos < M per evaluated layer), how many of them the float32 canonical-order
 oracle decides differently, and a digest of the float64 decisions.  Calls only oracle/ (through
 tests/margins.py) and the input generator; asserts on the way that every difference between the two
 oracles is a fragile decision.
 
-    python tests/golden/make_margin_audit.py [config ...]      (default: 1 2 3 4 5 6 7; a few minutes)
+    python tests/golden/make_margin_audit.py [config ...]      (default: 1 .. 8; a few minutes)
 """
 import hashlib
 import json
@@ -61,7 +61,7 @@ def audit_config(index: int, threads: int = 8) -> dict:
 
 
 def main() -> None:
-    which = [int(x) for x in sys.argv[1:]] or [1, 2, 3, 4, 5, 6, 7]
+    which = [int(x) for x in sys.argv[1:]] or [1, 2, 3, 4, 5, 6, 7, 8]
     out = json.load(open(PATH)) if os.path.exists(PATH) else {}
     out["bands"] = {"score": margins.BAND_SCORE, "ratio_times_f": margins.BAND_RATIO, "cos": margins.BAND_COS, "M": M}
     for i in which:

@@ -123,7 +123,7 @@ def workloads():
     return get
 
 
-@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_prune_tokens_on_config(workloads, index):
     cfg, tok = workloads(index)
     print(f"config {index}: {cfg.name} frames={tok.n_total} f={cfg.f} d={cfg.d}", flush=True)
@@ -137,7 +137,7 @@ def test_prune_tokens_on_config(workloads, index):
         {k: want[k] for k in ("k_fragile", "topk_fragile", "k_differs", "sets_differ")}
 
 
-@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_prune_kv_on_config(workloads, index):
     cfg, tok = workloads(index)
     lay = wl.kv_layout_for(cfg)

@@ -21,7 +21,7 @@ GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "margin_
 def test_record_covers_every_configuration_and_layer():
     assert GOLD["bands"] == {"score": margins.BAND_SCORE, "ratio_times_f": margins.BAND_RATIO,
                              "cos": margins.BAND_COS, "M": 0.2}
-    for i in range(1, 8):
+    for i in range(1, 9):
         cfg = wl.config(i)
         rec = GOLD[str(i)]
         assert rec["config"] == cfg.name

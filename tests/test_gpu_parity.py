@@ -190,6 +190,17 @@ def small_video(seed, n, f, d, dtype, rho=0.8, cuts=()):
     (4352, 5, 256, wl.BF16),      # 17 per workgroup: a full window and one frame more
     (8448, 3, 256, wl.BF16),      # 33: two windows and one
     (2100, 6, 512, wl.BF16),      # two slabs, runs of 16-17 frames, one of them across the slab boundary
+    # the two-kernel path (frames taller than 208 tokens, float32): sweeps per row, ragged last sweeps, runs of frames
+    (3, 300, 2056, wl.BF16),      # five sweeps, the last one ragged
+    (2, 210, 4096, wl.BF16),      # eight full sweeps: the widest row that is unrolled
+    (2, 250, 3080, wl.BF16),      # seven sweeps, ragged
+    (2, 222, 4104, wl.BF16),      # one chunk past the unrolled sweeps: the looped row kernel
+    (60, 300, 264, wl.BF16),      # runs of five frames per wavefront, twelve runs
+    (101, 209, 64, wl.BF16),      # runs of six, the last run shorter; 209 slots = 52 workgroups and one wavefront more
+    (3, 40, 2048, wl.F32),        # float32, four full sweeps
+    (3, 40, 1800, wl.F32),        # float32, four sweeps, ragged
+    (2, 30, 2056, wl.F32),        # float32 past the unrolled sweeps
+    (90, 50, 520, wl.F32),        # float32, runs of two frames
 ])
 def test_prune_tokens_shapes(n, f, d, dtype):
     tok = small_video(500 + n * 7 + f, n, f, d, dtype, cuts=(n // 2,) if n > 2 else ())

@@ -116,14 +116,28 @@ constexpr int kSlabWindow = 16;                           // frames whose shares
 constexpr int kSlabStage = kSlabWindow * 208 + 64;        // a window of frames (f <= 208) plus the row slots past the last
 constexpr int kSlabStageTotal = 256 + 3 * kSlabStage;     // a spare row, then x.x, x.x_prev, x.mean
 
-template <int KR>
-__device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const int n, const int f, const int d,
+//
+// A workgroup whose share crosses into the next slab would stop in mid-work to wait for two fresh frame
+// slabs, and finish that much later than the others.  So the buffers belong to the workgroup, not to
+// the run: where a run ends with the sequence, another run follows in the same workgroup, the last
+// frame sits in A (an even number of frames) and the next slab has all its columns, the last step's
+// refill of B (which past the sequence's end would fetch nothing of use) takes frame 0 of the next
+// slab, 32 chunks further along the same rows.  The run then returns true, and the run that follows
+// is one that finds B on its way (PRELOADED) and asks only for A.
+template <int KR, bool PRELOADED>
+__device__ __forceinline__ bool slab_run(const bf16_t* __restrict__ feats, const int n, const int f, const int d,
                                          const int nslabs, const int slab, const int t0, const int t1,
                                          float* __restrict__ part_aa, float* __restrict__ part_am,
                                          float* __restrict__ part_ab, float* __restrict__ part_mm,
                                          float (&sm)[16][kSlabRowLds], float (&smean)[kSlabRowLds],
-                                         float (&sstage)[kSlabStageTotal]) {
-    const int tid = threadIdx.x;
+                                         float (&sstage)[kSlabStageTotal], RawChunk<bf16_t> (&A)[KR],
+                                         RawChunk<bf16_t> (&B)[KR], const bool run_follows) {
+    // Opaque to the compiler, so that what a run derives from the thread index is derived anew by
+    // every run: hoisted out of the caller's loop over runs, those values would stay alive through the
+    // steps next to the two buffers, beyond the register file.
+    int tid_opaque = threadIdx.x;
+    asm volatile("" : "+v"(tid_opaque));
+    const int tid = tid_opaque;
     const int l = tid & 31;
     const int g = tid >> 5;
     const int nchunks = d / kChunk;
@@ -212,21 +226,25 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
         }
     };
 
-    RawChunk<bf16_t> A[KR], B[KR];
     float m[8];                                  // this lane's chunk of the latest frame-mean slab
 #pragma unroll
     for (int j = 0; j < 8; ++j) m[j] = 0.0f;
 
     const bool extra = t1 < n;                   // this run also makes x.x_prev of the next run's first frame
+    // what a refill past the sequence's end fetches: frame 0 of the next slab, else the last frame again
+    const bool hand_over = !PRELOADED && run_follows && !extra && ((t1 - t0) & 1) == 0 &&
+                           (slab + 2) * kBlockChunks <= nchunks;
+    const char* const past_end = hand_over ? fbase + (size_t)kBlockChunks * kChunk * sizeof(bf16_t)
+                                           : fbase + (size_t)(n - 1) * frame_bytes;
     auto step = [&](RawChunk<bf16_t> (&prev)[KR], RawChunk<bf16_t> (&curr)[KR], const int t, auto with_prev_c,
                     auto curr_stats_c) {
         constexpr bool with_prev = decltype(with_prev_c)::value;       // false: the run's first frame
         constexpr bool curr_stats = decltype(curr_stats_c)::value;     // false: the extra step (frame t1)
-        // A full step always refills (past the sequence's end: its last frame once more, never used), so
-        // that the loads sit under no condition.
+        // A full step always refills (past the sequence's end: see past_end), so that the loads sit under
+        // no condition.
         constexpr bool has_next = with_prev && curr_stats;
         const bool store_ab = with_prev && t > 0;
-        const char* const nb = fbase + (size_t)(t + 1 < n ? t + 1 : n - 1) * frame_bytes;
+        const char* const nb = t + 1 < n ? fbase + (size_t)(t + 1) * frame_bytes : past_end;
         float* const pp = pair_ptr + (size_t)t * f;
         // column sums: rows of class g (even k) and class g+16 (odd k), each ascending; the
         // stride-16 level of the class tree adds the two right here
@@ -364,8 +382,10 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
     {
         const char* const b1 = fbase + (size_t)t0 * frame_bytes;
         const char* const b2 = fbase + (size_t)(t0 + 1 < n ? t0 + 1 : n - 1) * frame_bytes;
+        if constexpr (!PRELOADED) {
 #pragma unroll
-        for (int k = 0; k < KR; ++k) B[k].q = load_stream(reinterpret_cast<const uint4*>(b1 + off[k]));
+            for (int k = 0; k < KR; ++k) B[k].q = load_stream(reinterpret_cast<const uint4*>(b1 + off[k]));
+        }
 #pragma unroll
         for (int k = 0; k < KR; ++k) A[k].q = load_stream(reinterpret_cast<const uint4*>(b2 + off[k]));
     }
@@ -384,6 +404,7 @@ __device__ __forceinline__ void slab_run(const bf16_t* __restrict__ feats, const
         if (extra) step(B, A, t1, yes, no); else tail(B, t1 - 1);
     }
     if (wj > 0) flush();
+    return hand_over;
 }
 
 // The (slab, frame) pairs, slab-major, are dealt out in equal contiguous runs, one per workgroup
@@ -406,12 +427,24 @@ __global__ __launch_bounds__(kSlabThreads) void frame_slab_kernel(const bf16_t* 
     const int w = blockIdx.x;
     long long u = (long long)w * run_len + (w < run_extra ? w : run_extra);   // nslabs * n may pass 2^31
     const long long u_end = u + run_len + (w < run_extra ? 1 : 0);
-    while (u < u_end) {
-        const int slab = (int)(u / n);
-        const int t0 = (int)(u - (long long)slab * n);
-        const int t1 = (long long)t0 + (u_end - u) < n ? t0 + (int)(u_end - u) : n;
-        slab_run<KR>(feats, n, f, d, nslabs, slab, t0, t1, part_aa, part_am, part_ab, part_mm, sm, smean, sstage);
-        u += t1 - t0;
+    int slab = (int)(u / n);
+    int t0 = (int)(u - (long long)slab * n);
+    long long left = u_end - u;                  // pairs still to do; every run after the first starts a slab
+    RawChunk<bf16_t> A[KR], B[KR];               // the two frame slabs in flight (see slab_run)
+    while (left > 0) {
+        int t1 = (long long)t0 + left < n ? t0 + (int)left : n;
+        left -= t1 - t0;
+        const bool handed = slab_run<KR, false>(feats, n, f, d, nslabs, slab, t0, t1, part_aa, part_am, part_ab,
+                                                  part_mm, sm, smean, sstage, A, B, left > 0);
+        ++slab;
+        t0 = 0;
+        if (handed) {                            // the next run finds its first frame on its way
+            t1 = left < n ? (int)left : n;
+            left -= t1;
+            slab_run<KR, true>(feats, n, f, d, nslabs, slab, 0, t1, part_aa, part_am, part_ab, part_mm, sm, smean,
+                               sstage, A, B, false);
+            ++slab;
+        }
     }
 }
 

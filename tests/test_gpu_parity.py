@@ -190,6 +190,11 @@ def small_video(seed, n, f, d, dtype, rho=0.8, cuts=()):
     (4352, 5, 256, wl.BF16),      # 17 per workgroup: a full window and one frame more
     (8448, 3, 256, wl.BF16),      # 33: two windows and one
     (2100, 6, 512, wl.BF16),      # two slabs, runs of 16-17 frames, one of them across the slab boundary
+    # workgroups whose share crosses a slab boundary (runs of 8-9 pairs on 256 compute units): the part before the
+    # boundary has an even or odd number of frames, the slab behind it is full or ragged
+    (701, 20, 520, wl.BF16),      # 6 frames, then a full slab; 3 frames, then the ragged last slab (one chunk)
+    (705, 20, 768, wl.BF16),      # three full slabs: 6 frames before the first boundary, 7 before the second
+    (702, 20, 768, wl.BF16),      # 4 frames, then 2 frames before the last slab
     # the two-kernel path (frames taller than 208 tokens, float32): sweeps per row, ragged last sweeps, runs of frames
     (3, 300, 2056, wl.BF16),      # five sweeps, the last one ragged
     (2, 210, 4096, wl.BF16),      # eight full sweeps: the widest row that is unrolled

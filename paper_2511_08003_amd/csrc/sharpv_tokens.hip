@@ -661,7 +661,12 @@ static void launch_token_dots(const TokArgs& a, const TokWorkspace& ws) {
 }
 
 // ---------------------------------------------------------------------------- scores, ratio, top-k
-__global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restrict__ mean,      // [n][d] or nullptr
+// SB = share loads per array in flight per thread.  16 takes the 14 shares of the model width in one
+// round trip but holds 64 loaded values (76 VGPRs: one 1024-thread workgroup per compute unit); 8 fits
+// 64 VGPRs, so that two workgroups share a compute unit when there are more frames than compute units.
+// The shares are added in ascending order either way.
+template <int SB>
+__global__ __launch_bounds__(1024, SB == 8 ? 8 : 4) void frame_select_kernel(const float* __restrict__ mean,      // [n][d] or nullptr
                                                             const float* __restrict__ part_mm,   // [n][nparts] if mean == nullptr
                                                             const float* __restrict__ aa, const float* __restrict__ am,
                                                             const float* __restrict__ ab,        // each [nparts][n*f]
@@ -696,7 +701,7 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
     const int nblocks = (nchunks + kBlockChunks - 1) / kBlockChunks;
 
     // Inner-product shares of this thread's token, summed in ascending block order (a single share
-    // when the rows were summed whole).  The loads come first and in batches of 16 shares x 4 arrays,
+    // when the rows were summed whole).  The loads come first and in batches of SB shares x 4 arrays,
     // so that their latency overlaps the mean.mean and first-frame work below; indices are clamped
     // (no load under a predicate) and all four arrays are read whether or not the frame turns out to
     // be a first frame (x.x_prev of frame 0 is never written and never used).
@@ -711,10 +716,10 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
         xp = ab[r];
         pp = aa[rprev];
     }
-    for (int s0 = 0; nparts > 1 && part == 0 && s0 < nparts; s0 += 16) {
-        float va[16], vm[16], vb[16], vp[16];
+    for (int s0 = 0; nparts > 1 && part == 0 && s0 < nparts; s0 += SB) {
+        float va[SB], vm[SB], vb[SB], vp[SB];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < SB; ++k) {
             const int sb = s0 + k < nparts ? s0 + k : nparts - 1;
             const size_t o = (size_t)sb * part_stride;
             va[k] = aa[o + r];
@@ -723,7 +728,7 @@ __global__ __launch_bounds__(1024) void frame_select_kernel(const float* __restr
             vp[k] = aa[o + rprev];
         }
 #pragma unroll
-        for (int k = 0; k < 16; ++k)
+        for (int k = 0; k < SB; ++k)
             if (s0 + k < nparts) {
                 xx = xx + va[k];
                 xm = xm + vm[k];
@@ -1004,11 +1009,17 @@ int launch_prune_tokens(const TokArgs& a) {
         TimedLaunch tl(kFrameSelect, st);
         const int tpp = (a.f + 63) / 64 * 64;
         const int parts = 1024 / tpp;            // >= 1 since f <= 1024
-        hipLaunchKernelGGL(frame_select_kernel, dim3(a.n), dim3(tpp * parts), 0, st,
-                           fused ? (const float*)nullptr : (const float*)ws.mean, (const float*)ws.part_mm,
-                           (const float*)ws.aa, (const float*)ws.am, (const float*)ws.ab, ws.nparts, (size_t)n_rows,
-                           a.frame_offsets, a.B, a.f, a.d, a.w, a.mode, a.K, a.min_keep, a.measure, tpp, ws.local_idx, a.out_counts,
-                           a.out_scores, a.out_ratio);
+        // more frames than compute units: the variant of which two workgroups fit a compute unit
+        const bool two_per_cu = a.n > num_compute_units();
+#define SHARPV_SELECT_LAUNCH(SB)                                                                                    \
+    hipLaunchKernelGGL(frame_select_kernel<SB>, dim3(a.n), dim3(tpp * parts), 0, st,                                \
+                       fused ? (const float*)nullptr : (const float*)ws.mean, (const float*)ws.part_mm,             \
+                       (const float*)ws.aa, (const float*)ws.am, (const float*)ws.ab, ws.nparts, (size_t)n_rows,    \
+                       a.frame_offsets, a.B, a.f, a.d, a.w, a.mode, a.K, a.min_keep, a.measure, tpp, ws.local_idx,  \
+                       a.out_counts, a.out_scores, a.out_ratio)
+        if (two_per_cu) SHARPV_SELECT_LAUNCH(8);
+        else SHARPV_SELECT_LAUNCH(16);
+#undef SHARPV_SELECT_LAUNCH
     }
     if (hipGetLastError() != hipSuccess) return SHARPV_ERR_DEVICE;
 
